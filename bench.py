@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the DiffQKV attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode_32k]
+
+A step is one pass of the whole path over one batch of synthetic input: for the decode workloads a
+`diffqkv_decode` / `diffqkv_decode_paged` call (split kernel + log-sum-exp combine), for the prefill
+workload a `diffqkv_prefill` call.  Inputs are resident in HBM before the timed region.  Consecutive
+steps rotate through several copies of the cache at distinct addresses so that the 256 MB
+last-level cache cannot serve a step from what the previous one left behind.
+
+Prints one JSON line.  `value` is whole-job throughput: KV-cache bytes read per second (decode) or
+attention TFLOP/s (prefill), from the wall clock around exactly K steps.  `roofline` is for the
+dominant kernel alone, timed with HIP events recorded on the launch stream; `cpu_baseline` is the
+float64 oracle on the host cores, for context only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+ROTATE_BYTES = 2.5e9        # keep at least this many distinct cache bytes in rotation
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="decode_32k",
+                    choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0, help="override tokens per context split (experiments)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); nothing in it uses a second device",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2501_13629_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    binding.load_library()  # fail loudly if the HIP library is not built
+    binding.diffqkv_set_tuning(decode_chunk_tokens=args.chunk)
+    dev = torch.device("cuda:0")
+    cfg = inputs.config(args.workload)
+    kind = cfg["kind"]
+    props = torch.cuda.get_device_properties(0)
+
+    # ---- inputs, resident on the device ----------------------------------------------------------
+    if kind == "decode":
+        host = inputs.make_decode(cfg)
+        kv_bytes = cfg["B"] * cfg["T"] * inputs.kv_bytes_per_token(cfg)
+        cache_names = ("k", "v")
+    elif kind == "paged":
+        host = inputs.make_paged(cfg)
+        kv_bytes = int(host["seqlens"].sum().item()) * inputs.kv_bytes_per_token(cfg)
+        cache_names = ("k_pool", "v_pool")
+    else:
+        host = inputs.make_prefill(cfg)
+        kv_bytes = 0
+        cache_names = ()
+    q = host["q"].to(dev)
+    set_bytes = sum(host[n].numel() * host[n].element_size() for n in cache_names)
+    n_sets = 1 if not cache_names else max(2, min(8, int(-(-ROTATE_BYTES // max(set_bytes, 1)))))
+    sets = []
+    for i in range(n_sets):
+        sets.append({n: (host[n].to(dev) if i == 0 else sets[0][n].clone()) for n in cache_names})
+    if kind == "paged":
+        bt, sl = host["block_table"].to(dev), host["seqlens"].to(dev)
+        max_T = host["max_pages"] * host["page_size"]
+    if kind != "prefill":
+        ws_bytes = binding.diffqkv_decode_workspace_bytes(cfg["B"], cfg["n_q"], cfg["n_k"], cfg["n_v"], cfg["d_qk"],
+                                                          cfg["d_v"], binding.BF16,
+                                                          cfg["T"] if kind == "decode" else max_T)
+        workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        out = torch.empty((cfg["B"], cfg["n_q"], cfg["d_v"]), dtype=q.dtype, device=dev)
+    else:
+        k_dev, v_dev = host["k"].to(dev), host["v"].to(dev)
+        out = torch.empty((cfg["B"], cfg["n_q"], cfg["S"], cfg["d_v"]), dtype=q.dtype, device=dev)
+        S = cfg["S"]
+        flops = 4.0 * cfg["d_qk"] * cfg["B"] * cfg["n_q"] * S * (S + 1) / 2  # masked half not counted
+
+    def step(i):
+        if kind == "decode":
+            s = sets[i % n_sets]
+            binding.diffqkv_decode(q, s["k"], s["v"], out=out, workspace=workspace)
+        elif kind == "paged":
+            s = sets[i % n_sets]
+            binding.diffqkv_decode_paged(q, s["k_pool"], s["v_pool"], bt, sl, out=out, workspace=workspace)
+        else:
+            binding.diffqkv_prefill(q, k_dev, v_dev, causal=True, out=out)
+
+    # ---- warm-up, then exactly K timed steps -------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ---- the dominant kernel alone, with events on the launch stream ----------------------------------
+    # decode: start event -> [split kernel] -> library-recorded event -> [combine] -> end event
+    n_ev = min(args.steps, 100)
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    for i in range(n_ev):
+        if kind != "prefill":
+            ev1[i].record()  # creates the underlying HIP event before handing it to the library
+            binding.diffqkv_set_split_event(ev1[i])
+        ev0[i].record()
+        step(i)
+        ev2[i].record()
+    binding.diffqkv_set_split_event(None)
+    torch.cuda.synchronize()
+    if kind != "prefill":
+        main_us = sorted(ev0[i].elapsed_time(ev1[i]) * 1e3 for i in range(n_ev))
+        tail_us = sorted(ev1[i].elapsed_time(ev2[i]) * 1e3 for i in range(n_ev))
+    else:
+        main_us = sorted(ev0[i].elapsed_time(ev2[i]) * 1e3 for i in range(n_ev))
+        tail_us = [0.0]
+    avg_main_us = sum(main_us) / len(main_us)
+
+    # ---- stream-read ceiling of this machine, over the same byte count -----------------------------------
+    ceiling = None
+    if kind != "prefill":
+        sink = torch.empty(4096, dtype=torch.float32, device=dev)
+        bufs = [torch.cat([s[n].reshape(-1) for n in cache_names]) for s in sets[: min(n_sets, 4)]]
+        for b in bufs:
+            binding.diffqkv_probe_stream_read(b, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5 * len(bufs)
+        e0.record()
+        for r in range(reps):
+            binding.diffqkv_probe_stream_read(bufs[r % len(bufs)], sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ceiling = bufs[0].numel() * bufs[0].element_size() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del bufs
+
+    # ---- result ------------------------------------------------------------------------------------
+    if kind != "prefill":
+        value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+        metric, unit = "decode-attention achieved HBM GB/s", "GB/s"
+        achieved = kv_bytes / (avg_main_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "kernel": "decode_mfma_kernel (split)", "kernel_avg_us": round(avg_main_us, 2),
+                "kernel_min_us": round(main_us[0], 2), "combine_avg_us": round(sum(tail_us) / len(tail_us), 2),
+                "algorithmic_bytes_per_launch": kv_bytes,
+                "stream_read_ceiling_GBps": None if ceiling is None else round(ceiling, 1)}
+    else:
+        value = flops / (ms_per_step * 1e-3) / 1e12
+        metric, unit = "causal-prefill attention TFLOP/s", "TFLOP/s"
+        achieved = flops / (avg_main_us * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "prefill kernel",
+                "kernel_avg_us": round(avg_main_us, 2), "kernel_min_us": round(main_us[0], 2),
+                "algorithmic_flops_per_launch": flops}
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc (see profiles/)
+        with open(traffic_file) as f:
+            roof["traffic"] = json.load(f).get(args.workload)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, host, kind, kv_bytes)
+
+    line = {
+        "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4) if kind != "prefill" else None,
+        "config": {"workload": args.workload, **{k: v for k, v in cfg.items()
+                                                 if k in ("B", "n_q", "n_k", "n_v", "d_qk", "d_v", "T", "S", "page_size")},
+                   "kv_bytes_per_step": kv_bytes, "cache_sets_in_rotation": n_sets,
+                   "device": props.name, "compute_units": props.multi_processor_count},
+        "roofline": roof, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(cfg, host, kind, kv_bytes):
+    """The float64 oracle as it stands, on the host cores, over a bounded sample of the workload."""
+    import numpy as np
+
+    import oracle
+    from paper_2501_13629_amd import inputs
+
+    a = inputs.as_numpy
+    threads = oracle.num_threads()
+    if kind == "decode":
+        fn = lambda: oracle.decode(a(host["q"]), a(host["k"]), a(host["v"]))
+        work, unit, sample = kv_bytes / 1e9, "GB/s", "the full workload, one evaluation"
+    elif kind == "paged":
+        n = 16  # sequences
+        fn = lambda: oracle.decode_paged(a(host["q"])[:n], a(host["k_pool"]), a(host["v_pool"]),
+                                         host["block_table"].numpy()[:n], host["seqlens"].numpy()[:n])
+        work = int(host["seqlens"][:n].sum().item()) * inputs.kv_bytes_per_token(cfg) / 1e9
+        unit, sample = "GB/s", "the first %d of %d sequences, one evaluation" % (n, cfg["B"])
+    else:
+        rows = np.arange(0, cfg["S"], 128, dtype=np.int32)  # every 128th query row, all heads
+        fn = lambda: oracle.prefill(a(host["q"]), a(host["k"]), a(host["v"]), causal=True, rows=rows)
+        work = float(sum(4.0 * cfg["d_qk"] * cfg["B"] * cfg["n_q"] * (int(i) + 1) for i in rows)) / 1e12
+        unit, sample = "TFLOP/s", "every 128th query row of every head (%d rows), one evaluation" % len(rows)
+    t0 = time.perf_counter()
+    fn()
+    dt = time.perf_counter() - t0
+    return {"value": round(work / dt, 4), "unit": unit, "cores": threads, "kind": "oracle", "sample": sample,
+            "seconds": round(dt, 3)}
+
+
+if __name__ == "__main__":
+    main()

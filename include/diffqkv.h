@@ -1,0 +1,163 @@
+/*
+ * diffqkv -- DiffQKV attention over an asymmetric KV cache, for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Every entry point takes plain pointers and sizes; there are no C++ or
+ * framework types in any signature and no exception crosses this boundary.
+ *
+ * The operation (paper section 2, "Formulation of DiffQKV Attention"): queries have n_q heads, the
+ * key cache n_k heads, the value cache n_v heads, with n_k and n_v both dividing n_q.  Query head h
+ * reads K head  kh = floor(h * n_k / n_q)  and V head  vh = floor(h * n_v / n_q)  (GroupSharing;
+ * head-index rule "idx" of section 3.2, "Flexible Attention Computation"), and
+ *
+ *     out[b,h,:] = sum_j softmax_j( scale * <q[b,h,:], K[b,kh,j,:]> ) * V[b,vh,j,:],   j < T_b.
+ *
+ * K is therefore streamed once per K head and V once per V head; nothing is ever expanded to n_q
+ * (or to n_v) heads in memory, which is what the cost model of section 3.2 ("KV Cache") counts.
+ *
+ * Conventions common to all calls
+ *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns every
+ *     buffer; the library never allocates, frees or synchronises: it validates on the host and
+ *     enqueues kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Inputs are read-only.  `out` is fully overwritten.  `workspace` contents are undefined after
+ *     the call.  Two calls may not share a workspace concurrently.
+ *   - Strides are in ELEMENTS of the tensor's dtype.  The innermost (channel) stride is always 1.
+ *     Base pointers and all strides must keep every row 16-byte aligned.
+ *   - The current token's k_t, v_t are already in the cache when attention runs (the paper
+ *     concatenates before attending), so a live sequence has T_b >= 1.  A sequence with T_b == 0
+ *     produces out = 0 and lse = -inf.
+ *   - Cache memory beyond T_b (the tail of the last page, unused capacity) may hold anything,
+ *     including NaN; it never influences the result.
+ *   - Return value: a diffqkv_status.  On any value other than DIFFQKV_OK nothing was enqueued.
+ *     Errors raised asynchronously by the device surface at the caller's next synchronisation.
+ *   - Results are a deterministic function of the arguments (no atomics in any reduction).
+ */
+#ifndef DIFFQKV_H_
+#define DIFFQKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DIFFQKV_F32 = 0, DIFFQKV_BF16 = 1 } diffqkv_dtype;
+
+typedef enum {
+  DIFFQKV_OK = 0,
+  DIFFQKV_ERR_NULL = -1,        /* a required pointer is NULL                                      */
+  DIFFQKV_ERR_SHAPE = -2,       /* a count is <= 0, a head width is unsupported, S_k < S_q, ...    */
+  DIFFQKV_ERR_HEADS = -3,       /* n_k or n_v does not divide n_q, or neither of n_k, n_v divides
+                                   the other                                                       */
+  DIFFQKV_ERR_ALIGN = -4,       /* a base pointer or stride breaks 16-byte row alignment           */
+  DIFFQKV_ERR_WORKSPACE = -5,   /* workspace is NULL or smaller than the *_workspace_bytes figure  */
+  DIFFQKV_ERR_UNSUPPORTED = -6, /* valid arguments this build has no kernel for                    */
+  DIFFQKV_ERR_HIP = -7          /* a HIP call failed at launch time                                */
+} diffqkv_status;
+
+/* Problem shape shared by all calls.  Supported head widths: multiples of 8 up to 256 (the tuned
+ * kernels cover 64 and 128).  softmax_scale == 0 selects 1/sqrt(d_qk). */
+typedef struct {
+  int32_t B;     /* sequences in the batch                    */
+  int32_t n_q;   /* query heads                               */
+  int32_t n_k;   /* key heads   (divides n_q)                 */
+  int32_t n_v;   /* value heads (divides n_q)                 */
+  int32_t d_qk;  /* width of a query / key head               */
+  int32_t d_v;   /* width of a value head (= output width)    */
+  int32_t dtype; /* diffqkv_dtype of q, the caches and out    */
+  float softmax_scale;
+} diffqkv_shape;
+
+/* Optional knobs for experiments; zero fields mean "library default".  Process-global, not
+ * thread-safe: set once before issuing work. */
+typedef struct {
+  int32_t decode_chunk_tokens; /* tokens per context split (multiple of 128)                      */
+  int32_t force_generic;       /* 1: always take the portable kernels instead of the MFMA ones    */
+  int32_t reserved[6];
+} diffqkv_tuning;
+void diffqkv_set_tuning(const diffqkv_tuning* t /* host; NULL resets */);
+
+/*
+ * Split decode (section 3.2: "split kernel" producing per-chunk partial outputs, "combine kernel"
+ * merging them by log-sum-exp).  One query token per sequence against a contiguous cache.
+ *
+ *   q        [B, n_q, d_qk]   dense
+ *   k_cache  element (b, kh, j, c) at  b*k_stride_b + kh*k_stride_h + j*k_stride_t + c
+ *   v_cache  element (b, vh, j, e) at  b*v_stride_b + vh*v_stride_h + j*v_stride_t + e
+ *            (head-major [B, n, T_cap, d] and token-major [B, T_cap, n, d] are both expressible)
+ *   seqlens  int32 [B] on the device, or NULL: then every sequence has T tokens
+ *   T        with seqlens: an upper bound on every T_b (the cache capacity is a valid bound);
+ *            T_b is clamped to it.  T >= 0.
+ *   out      [B, n_q, d_v]   dtype of the inputs
+ *   lse_out  float [B, n_q] natural-log sum of exp of the scaled scores, or NULL
+ *   workspace/workspace_bytes  at least diffqkv_decode_workspace_bytes(shape, T) bytes, 256-byte
+ *            aligned; holds the per-split partial outputs and their log-sum-exps
+ */
+size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape /* host */, int32_t max_T);
+int diffqkv_decode(const diffqkv_shape* shape /* host */, const void* q, const void* k_cache,
+                   const void* v_cache, int64_t k_stride_b, int64_t k_stride_h, int64_t k_stride_t,
+                   int64_t v_stride_b, int64_t v_stride_h, int64_t v_stride_t,
+                   const int32_t* seqlens, int32_t T, void* out, float* lse_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Split decode over a paged cache (the paper only cites paged attention; the layout is this
+ * library's).  Logical token j of sequence b is slot j % page_size of physical page
+ * block_table[b * max_pages + j / page_size].  K and V share the block table.
+ *
+ *   k_pool   element (page, kh, slot, c) at  page*k_stride_page + kh*k_stride_h + slot*k_stride_t + c
+ *   v_pool   element (page, vh, slot, e) at  page*v_stride_page + vh*v_stride_h + slot*v_stride_t + e
+ *            (the tuned layout is head-major inside a page: [n_pages, n, page_size, d])
+ *   block_table  int32 [B, max_pages] on the device; entries past ceil(T_b / page_size) are ignored
+ *   page_size    tokens per page, > 0; multiples of 16 take the tuned kernel
+ *   seqlens      int32 [B] on the device (required); 0 <= T_b <= max_pages * page_size
+ *   workspace    at least diffqkv_decode_workspace_bytes(shape, max_pages * page_size) bytes
+ * Page ids are not range-checked on the device: the caller guarantees they index the pools.
+ */
+int diffqkv_decode_paged(const diffqkv_shape* shape /* host */, const void* q, const void* k_pool,
+                         const void* v_pool, int64_t k_stride_page, int64_t k_stride_h,
+                         int64_t k_stride_t, int64_t v_stride_page, int64_t v_stride_h,
+                         int64_t v_stride_t, const int32_t* block_table, int32_t max_pages,
+                         int32_t page_size, const int32_t* seqlens, void* out, float* lse_out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Prefill: the same attention for a block of S_q query positions against S_k keys (section 2: K_t
+ * holds the t tokens up to the current one, so query i attends to positions <= i).  With
+ * causal != 0 the mask is aligned to the newest token: query i sees keys j <= i + (S_k - S_q), so
+ * S_q = 1 is exactly the decode case.  Requires S_k >= S_q when causal.
+ *
+ *   q   [B, n_q, S_q, d_qk]   k [B, n_k, S_k, d_qk]   v [B, n_v, S_k, d_v]   dense, head-major
+ *   out [B, n_q, S_q, d_v]    lse_out float [B, n_q, S_q] or NULL
+ *   workspace: diffqkv_prefill_workspace_bytes(...) bytes (may be 0, then NULL is accepted)
+ */
+size_t diffqkv_prefill_workspace_bytes(const diffqkv_shape* shape /* host */, int32_t S_q, int32_t S_k);
+int diffqkv_prefill(const diffqkv_shape* shape /* host */, const void* q, const void* k,
+                    const void* v, int32_t S_q, int32_t S_k, int32_t causal, void* out,
+                    float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Measurement aid: reads `bytes` (a multiple of 16) from `src` with 128-bit loads, as fast as the
+ * memory system allows, and writes one float per workgroup to `sink` (at least 4096 floats) so the
+ * reads cannot be elided.  Used to measure the achievable HBM read rate beside the decode kernels.
+ */
+int diffqkv_probe_stream_read(const void* src, size_t bytes, float* sink, void* hip_stream);
+
+/*
+ * Measurement aid: when `hip_event` (a hipEvent_t passed as void*) is not NULL, every later decode
+ * call records it on its stream between the split kernel and the combine kernel, so a caller that
+ * brackets the call with two events of its own can time the two kernels separately.  NULL turns it
+ * off.  Process-global, not thread-safe.
+ */
+void diffqkv_set_split_event(void* hip_event);
+
+/* Human-readable text for a diffqkv_status (static storage). */
+const char* diffqkv_strerror(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int diffqkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIFFQKV_H_ */

@@ -1,0 +1,240 @@
+"""Thin ctypes binding of libdiffqkv.so -- argument marshalling only.
+
+Every step of the attention path runs inside the library's HIP kernels.  PyTorch appears here only
+as the owner of device memory and of the HIP stream.  There is no CPU fallback: if the library has
+not been built, or the tensors are not on a GPU, the calls raise.
+
+Functions carry the names of the C entry points in ``include/diffqkv.h``.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libdiffqkv.so"
+
+F32, BF16 = 0, 1
+
+EXPORTS = (
+    "diffqkv_set_tuning", "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_paged",
+    "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_probe_stream_read", "diffqkv_strerror",
+    "diffqkv_version", "diffqkv_set_split_event",
+)
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "n_q", "n_k", "n_v", "d_qk", "d_v", "dtype")] + [
+        ("softmax_scale", ctypes.c_float)
+    ]
+
+
+class Tuning(ctypes.Structure):
+    _fields_ = [("decode_chunk_tokens", ctypes.c_int32), ("force_generic", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 6)]
+
+
+class DiffQKVError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("diffqkv status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library.  Raises if it is missing: build it first with
+    ``python -m paper_2501_13629_amd.build`` (or ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        raise RuntimeError(
+            "%s not found: the HIP library has not been built "
+            "(run `python -m paper_2501_13629_amd.build`); there is no fallback path" % LIB_PATH
+        )
+    lib = ctypes.CDLL(str(LIB_PATH))
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    sp = ctypes.POINTER(Shape)
+    lib.diffqkv_set_tuning.restype = None
+    lib.diffqkv_set_tuning.argtypes = [ctypes.POINTER(Tuning)]
+    lib.diffqkv_decode_workspace_bytes.restype = sz
+    lib.diffqkv_decode_workspace_bytes.argtypes = [sp, i32]
+    lib.diffqkv_decode.restype = ctypes.c_int
+    lib.diffqkv_decode.argtypes = [sp, vp, vp, vp] + [i64] * 6 + [vp, i32, vp, vp, vp, sz, vp]
+    lib.diffqkv_decode_paged.restype = ctypes.c_int
+    lib.diffqkv_decode_paged.argtypes = [sp, vp, vp, vp] + [i64] * 6 + [vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.diffqkv_prefill_workspace_bytes.restype = sz
+    lib.diffqkv_prefill_workspace_bytes.argtypes = [sp, i32, i32]
+    lib.diffqkv_prefill.restype = ctypes.c_int
+    lib.diffqkv_prefill.argtypes = [sp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.diffqkv_probe_stream_read.restype = ctypes.c_int
+    lib.diffqkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.diffqkv_strerror.restype = ctypes.c_char_p
+    lib.diffqkv_strerror.argtypes = [ctypes.c_int]
+    lib.diffqkv_set_split_event.restype = None
+    lib.diffqkv_set_split_event.argtypes = [vp]
+    lib.diffqkv_version.restype = ctypes.c_int
+    lib.diffqkv_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise DiffQKVError(status, load_library().diffqkv_strerror(status).decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("diffqkv supports float32 and bfloat16 tensors, got %s" % t.dtype)
+
+
+def _dev(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("diffqkv runs on the GPU only: every tensor must be a device tensor")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, scale) -> Shape:
+    return Shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, 0.0 if scale is None else float(scale))
+
+
+def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False):
+    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0)
+    load_library().diffqkv_set_tuning(ctypes.byref(t))
+
+
+def diffqkv_set_split_event(event) -> None:
+    """`event`: a recorded-at-least-once torch.cuda.Event(enable_timing=True), or None to turn off."""
+    handle = None if event is None else ctypes.c_void_p(event.cuda_event)
+    load_library().diffqkv_set_split_event(handle)
+
+
+def diffqkv_version() -> int:
+    return int(load_library().diffqkv_version())
+
+
+def diffqkv_decode_workspace_bytes(B, n_q, n_k, n_v, d_qk, d_v, dtype, max_T) -> int:
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, None)
+    return int(load_library().diffqkv_decode_workspace_bytes(ctypes.byref(s), int(max_T)))
+
+
+def _workspace(nbytes: int, like: torch.Tensor, workspace):
+    if workspace is not None:
+        return workspace
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=like.device)
+
+
+def diffqkv_decode(q, k_cache, v_cache, seqlens=None, T=None, scale=None, out=None, lse_out=None,
+                   workspace=None, want_lse=False):
+    """q [B,n_q,d_qk]; k_cache [B,n_k,T_cap,d_qk]; v_cache [B,n_v,T_cap,d_v] (any batch/head/token
+    strides, channels contiguous); seqlens int32 device [B] or None.  Returns out, or (out, lse)."""
+    _dev(q, k_cache, v_cache, seqlens, out, lse_out, workspace)
+    dt = _dtype_code(q)
+    if _dtype_code(k_cache) != dt or _dtype_code(v_cache) != dt:
+        raise TypeError("q, k_cache and v_cache must share a dtype")
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    B, n_q, d_qk = q.shape
+    _, n_k, T_cap, _ = k_cache.shape
+    _, n_v, _, d_v = v_cache.shape
+    if k_cache.stride(3) != 1 or v_cache.stride(3) != 1:
+        raise ValueError("the channel dimension of the caches must be contiguous")
+    if T is None:
+        T = T_cap
+    if T > T_cap:
+        raise ValueError("T exceeds the cache capacity")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or not seqlens.is_contiguous()):
+        raise TypeError("seqlens must be a contiguous int32 tensor")
+    if out is None:
+        out = torch.empty((B, n_q, d_v), dtype=q.dtype, device=q.device)
+    if lse_out is None and want_lse:
+        lse_out = torch.empty((B, n_q), dtype=torch.float32, device=q.device)
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, scale)
+    lib = load_library()
+    need = int(lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), int(T)))
+    workspace = _workspace(need, q, workspace)
+    ks, vs = k_cache.stride(), v_cache.stride()
+    _check(lib.diffqkv_decode(
+        ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
+        _ptr(seqlens), int(T), _ptr(out), _ptr(lse_out), _ptr(workspace), workspace.numel(), _stream(q)))
+    return (out, lse_out) if (want_lse or lse_out is not None) else out
+
+
+def diffqkv_decode_paged(q, k_pool, v_pool, block_table, seqlens, scale=None, out=None, lse_out=None,
+                         workspace=None, want_lse=False):
+    """q [B,n_q,d_qk]; k_pool [n_pages,n_k,P,d_qk]; v_pool [n_pages,n_v,P,d_v]; block_table int32
+    device [B,max_pages]; seqlens int32 device [B]."""
+    _dev(q, k_pool, v_pool, block_table, seqlens, out, lse_out, workspace)
+    dt = _dtype_code(q)
+    if _dtype_code(k_pool) != dt or _dtype_code(v_pool) != dt:
+        raise TypeError("q, k_pool and v_pool must share a dtype")
+    if not q.is_contiguous() or not block_table.is_contiguous() or not seqlens.is_contiguous():
+        raise ValueError("q, block_table and seqlens must be contiguous")
+    if block_table.dtype != torch.int32 or seqlens.dtype != torch.int32:
+        raise TypeError("block_table and seqlens must be int32")
+    B, n_q, d_qk = q.shape
+    _, n_k, P, _ = k_pool.shape
+    _, n_v, _, d_v = v_pool.shape
+    if k_pool.stride(3) != 1 or v_pool.stride(3) != 1:
+        raise ValueError("the channel dimension of the pools must be contiguous")
+    max_pages = block_table.shape[1]
+    if out is None:
+        out = torch.empty((B, n_q, d_v), dtype=q.dtype, device=q.device)
+    if lse_out is None and want_lse:
+        lse_out = torch.empty((B, n_q), dtype=torch.float32, device=q.device)
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, scale)
+    lib = load_library()
+    need = int(lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), int(max_pages * P)))
+    workspace = _workspace(need, q, workspace)
+    ks, vs = k_pool.stride(), v_pool.stride()
+    _check(lib.diffqkv_decode_paged(
+        ctypes.byref(s), _ptr(q), _ptr(k_pool), _ptr(v_pool), ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
+        _ptr(block_table), int(max_pages), int(P), _ptr(seqlens), _ptr(out), _ptr(lse_out),
+        _ptr(workspace), workspace.numel(), _stream(q)))
+    return (out, lse_out) if (want_lse or lse_out is not None) else out
+
+
+def diffqkv_prefill(q, k, v, causal=True, scale=None, out=None, lse_out=None, want_lse=False):
+    """q [B,n_q,S_q,d_qk]; k [B,n_k,S_k,d_qk]; v [B,n_v,S_k,d_v], contiguous."""
+    _dev(q, k, v, out, lse_out)
+    dt = _dtype_code(q)
+    if _dtype_code(k) != dt or _dtype_code(v) != dt:
+        raise TypeError("q, k and v must share a dtype")
+    if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
+        raise ValueError("q, k and v must be contiguous")
+    B, n_q, S_q, d_qk = q.shape
+    _, n_k, S_k, _ = k.shape
+    _, n_v, _, d_v = v.shape
+    if out is None:
+        out = torch.empty((B, n_q, S_q, d_v), dtype=q.dtype, device=q.device)
+    if lse_out is None and want_lse:
+        lse_out = torch.empty((B, n_q, S_q), dtype=torch.float32, device=q.device)
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, scale)
+    _check(load_library().diffqkv_prefill(
+        ctypes.byref(s), _ptr(q), _ptr(k), _ptr(v), int(S_q), int(S_k), 1 if causal else 0, _ptr(out),
+        _ptr(lse_out), None, 0, _stream(q)))
+    return (out, lse_out) if (want_lse or lse_out is not None) else out
+
+
+def diffqkv_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor):
+    """Launch the stream-read probe over `buf` (any dtype, byte size a multiple of 16)."""
+    _dev(buf, sink)
+    nbytes = buf.numel() * buf.element_size()
+    assert sink.dtype == torch.float32 and sink.numel() >= 4096
+    _check(load_library().diffqkv_probe_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream(buf)))

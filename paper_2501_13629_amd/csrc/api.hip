@@ -1,0 +1,265 @@
+// The C ABI of libdiffqkv: argument validation, split planning and kernel dispatch.
+// Declarations and their documentation live in include/diffqkv.h.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/diffqkv.h"
+#include "kernels.h"
+
+using namespace diffqkv;
+
+namespace {
+
+diffqkv_tuning g_tuning = {};
+hipEvent_t g_split_event = nullptr;
+
+constexpr int kComputeUnits = 256;  // MI355X; the split plan is a pure function of the shapes
+constexpr int kTargetWorkgroups = 4 * kComputeUnits;
+constexpr int kChunkQuantum = 128;  // one workgroup step of the decode kernels
+constexpr int kMinChunk = 256;
+constexpr int kMaxChunk = 1024;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_size(int dtype) { return dtype == DIFFQKV_F32 ? 4 : 2; }
+inline bool stride_ok(int64_t stride, int dtype) { return stride >= 0 && (stride * (int64_t)elem_size(dtype)) % 16 == 0; }
+
+int check_shape(const diffqkv_shape* s) {
+  if (!s) return DIFFQKV_ERR_NULL;
+  if (s->B < 0 || s->n_q <= 0 || s->n_k <= 0 || s->n_v <= 0) return DIFFQKV_ERR_SHAPE;
+  if (s->d_qk < 8 || s->d_qk > 256 || s->d_qk % 8 || s->d_v < 8 || s->d_v > 256 || s->d_v % 8)
+    return DIFFQKV_ERR_SHAPE;
+  if (s->dtype != DIFFQKV_F32 && s->dtype != DIFFQKV_BF16) return DIFFQKV_ERR_SHAPE;
+  if (!(s->softmax_scale >= 0.f) || isinf(s->softmax_scale)) return DIFFQKV_ERR_SHAPE;
+  if (s->n_q % s->n_k || s->n_q % s->n_v) return DIFFQKV_ERR_HEADS;
+  const int hi = s->n_k > s->n_v ? s->n_k : s->n_v, lo = s->n_k > s->n_v ? s->n_v : s->n_k;
+  if (hi % lo) return DIFFQKV_ERR_HEADS;
+  return DIFFQKV_OK;
+}
+
+float scale_log2(const diffqkv_shape* s) {
+  const float scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->d_qk);
+  return scale * kLog2e;
+}
+
+// Context split: a pure function of the shapes so that results are repeatable bit for bit.
+void plan_decode(const diffqkv_shape* s, int32_t max_T, int32_t* chunk, int32_t* num_splits) {
+  int c;
+  if (g_tuning.decode_chunk_tokens > 0) {
+    c = (g_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+  } else {
+    const int groups = (s->n_k < s->n_v ? s->n_k : s->n_v) * (s->B > 0 ? s->B : 1);
+    const int64_t total = (int64_t)max_T * groups;
+    int64_t per = (total + kTargetWorkgroups - 1) / kTargetWorkgroups;
+    per = (per + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    c = (int)(per < kMinChunk ? kMinChunk : (per > kMaxChunk ? kMaxChunk : per));
+  }
+  *chunk = c;
+  int n = (int)(((int64_t)max_T + c - 1) / c);
+  *num_splits = n < 1 ? 1 : n;
+}
+
+size_t workspace_for(const diffqkv_shape* s, int32_t num_splits) {
+  if (num_splits <= 1) return 0;
+  size_t rows = (size_t)s->B * s->n_q * num_splits;
+  size_t bytes = rows * ((size_t)s->d_v + 1) * sizeof(float);
+  return (bytes + 255) / 256 * 256;
+}
+
+int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* workspace,
+               size_t workspace_bytes, hipStream_t stream) {
+  plan_decode(s, p.T, &p.chunk, &p.num_splits);
+  const size_t need = workspace_for(s, p.num_splits);
+  if (need) {
+    if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DIFFQKV_ERR_ALIGN;
+  }
+  p.B = s->B;
+  p.n_q = s->n_q;
+  p.n_k = s->n_k;
+  p.n_v = s->n_v;
+  p.d_qk = s->d_qk;
+  p.d_v = s->d_v;
+  p.n_groups = s->n_k < s->n_v ? s->n_k : s->n_v;
+  p.G = s->n_q / p.n_groups;
+  p.scale_log2 = scale_log2(s);
+  p.o_part = (float*)workspace;
+  p.lse_part = need ? p.o_part + (size_t)s->B * s->n_q * p.num_splits * s->d_v : nullptr;
+  if (s->B == 0) return DIFFQKV_OK;
+  hipError_t e;
+  if (!g_tuning.force_generic && decode_mfma_supported(p, s->dtype))
+    e = launch_decode_mfma(p, paged, stream);
+  else
+    e = launch_decode_generic(p, s->dtype, paged, stream);
+  if (e != hipSuccess) return DIFFQKV_ERR_HIP;
+  if (g_split_event && hipEventRecord(g_split_event, stream) != hipSuccess) return DIFFQKV_ERR_HIP;
+  if (p.num_splits > 1) {
+    e = launch_combine(p, s->dtype, stream);
+    if (e != hipSuccess) return DIFFQKV_ERR_HIP;
+  }
+  return DIFFQKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void diffqkv_set_tuning(const diffqkv_tuning* t) {
+  if (t)
+    g_tuning = *t;
+  else
+    memset(&g_tuning, 0, sizeof g_tuning);
+}
+
+void diffqkv_set_split_event(void* hip_event) { g_split_event = (hipEvent_t)hip_event; }
+
+size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape, int32_t max_T) {
+  if (check_shape(shape) != DIFFQKV_OK || max_T < 0) return 0;
+  int32_t chunk, splits;
+  plan_decode(shape, max_T, &chunk, &splits);
+  return workspace_for(shape, splits);
+}
+
+int diffqkv_decode(const diffqkv_shape* shape, const void* q, const void* k_cache,
+                   const void* v_cache, int64_t k_stride_b, int64_t k_stride_h, int64_t k_stride_t,
+                   int64_t v_stride_b, int64_t v_stride_h, int64_t v_stride_t,
+                   const int32_t* seqlens, int32_t T, void* out, float* lse_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (T < 0) return DIFFQKV_ERR_SHAPE;
+  if (shape->B > 0) {
+    if (!q || !out) return DIFFQKV_ERR_NULL;
+    if (T > 0 && (!k_cache || !v_cache)) return DIFFQKV_ERR_NULL;
+  }
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
+    return DIFFQKV_ERR_ALIGN;
+  const int dt = shape->dtype;
+  if (!stride_ok(k_stride_b, dt) || !stride_ok(k_stride_h, dt) || !stride_ok(k_stride_t, dt) ||
+      !stride_ok(v_stride_b, dt) || !stride_ok(v_stride_h, dt) || !stride_ok(v_stride_t, dt))
+    return DIFFQKV_ERR_ALIGN;
+  if (k_stride_t < shape->d_qk || v_stride_t < shape->d_v) return DIFFQKV_ERR_SHAPE;
+  DecodeParams p = {};
+  p.q = q;
+  p.k = k_cache;
+  p.v = v_cache;
+  p.k_sb = k_stride_b;
+  p.k_sh = k_stride_h;
+  p.k_st = k_stride_t;
+  p.v_sb = v_stride_b;
+  p.v_sh = v_stride_h;
+  p.v_st = v_stride_t;
+  p.seqlens = seqlens;
+  p.T = T;
+  p.out = out;
+  p.lse_out = lse_out;
+  return run_decode(shape, p, false, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int diffqkv_decode_paged(const diffqkv_shape* shape, const void* q, const void* k_pool,
+                         const void* v_pool, int64_t k_stride_page, int64_t k_stride_h,
+                         int64_t k_stride_t, int64_t v_stride_page, int64_t v_stride_h,
+                         int64_t v_stride_t, const int32_t* block_table, int32_t max_pages,
+                         int32_t page_size, const int32_t* seqlens, void* out, float* lse_out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (max_pages < 0 || page_size <= 0) return DIFFQKV_ERR_SHAPE;
+  if ((int64_t)max_pages * page_size > INT32_MAX) return DIFFQKV_ERR_SHAPE;
+  if (shape->B > 0) {
+    if (!q || !out || !seqlens) return DIFFQKV_ERR_NULL;
+    if (max_pages > 0 && (!k_pool || !v_pool || !block_table)) return DIFFQKV_ERR_NULL;
+  }
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out))
+    return DIFFQKV_ERR_ALIGN;
+  const int dt = shape->dtype;
+  if (!stride_ok(k_stride_page, dt) || !stride_ok(k_stride_h, dt) || !stride_ok(k_stride_t, dt) ||
+      !stride_ok(v_stride_page, dt) || !stride_ok(v_stride_h, dt) || !stride_ok(v_stride_t, dt))
+    return DIFFQKV_ERR_ALIGN;
+  if (k_stride_t < shape->d_qk || v_stride_t < shape->d_v) return DIFFQKV_ERR_SHAPE;
+  DecodeParams p = {};
+  p.q = q;
+  p.k = k_pool;
+  p.v = v_pool;
+  p.k_sb = k_stride_page;
+  p.k_sh = k_stride_h;
+  p.k_st = k_stride_t;
+  p.v_sb = v_stride_page;
+  p.v_sh = v_stride_h;
+  p.v_st = v_stride_t;
+  p.seqlens = seqlens;
+  p.block_table = block_table;
+  p.max_pages = max_pages;
+  p.page_size = page_size;
+  p.T = max_pages * page_size;
+  p.out = out;
+  p.lse_out = lse_out;
+  return run_decode(shape, p, true, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+size_t diffqkv_prefill_workspace_bytes(const diffqkv_shape* shape, int32_t S_q, int32_t S_k) {
+  (void)shape;
+  (void)S_q;
+  (void)S_k;
+  return 0;  // the prefill kernels keep all running state on chip
+}
+
+int diffqkv_prefill(const diffqkv_shape* shape, const void* q, const void* k, const void* v,
+                    int32_t S_q, int32_t S_k, int32_t causal, void* out, float* lse_out,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int rc = check_shape(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (S_q <= 0 || S_k <= 0) return DIFFQKV_ERR_SHAPE;
+  if (causal && S_k < S_q) return DIFFQKV_ERR_SHAPE;
+  if (shape->B > 0 && (!q || !k || !v || !out)) return DIFFQKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return DIFFQKV_ERR_ALIGN;
+  PrefillParams p = {};
+  p.q = q;
+  p.k = k;
+  p.v = v;
+  p.out = out;
+  p.lse_out = lse_out;
+  p.B = shape->B;
+  p.n_q = shape->n_q;
+  p.n_k = shape->n_k;
+  p.n_v = shape->n_v;
+  p.d_qk = shape->d_qk;
+  p.d_v = shape->d_v;
+  p.S_q = S_q;
+  p.S_k = S_k;
+  p.causal = causal ? 1 : 0;
+  p.scale_log2 = scale_log2(shape);
+  if (shape->B == 0) return DIFFQKV_OK;
+  hipError_t e;
+  if (!g_tuning.force_generic && prefill_mfma_supported(p, shape->dtype))
+    e = launch_prefill_mfma(p, (hipStream_t)hip_stream);
+  else
+    e = launch_prefill_generic(p, shape->dtype, (hipStream_t)hip_stream);
+  return e == hipSuccess ? DIFFQKV_OK : DIFFQKV_ERR_HIP;
+}
+
+int diffqkv_probe_stream_read(const void* src, size_t bytes, float* sink, void* hip_stream) {
+  if (!src || !sink) return DIFFQKV_ERR_NULL;
+  if (bytes % 16 || !aligned16(src)) return DIFFQKV_ERR_ALIGN;
+  hipError_t e = launch_probe_stream_read(src, bytes, sink, (hipStream_t)hip_stream);
+  return e == hipSuccess ? DIFFQKV_OK : DIFFQKV_ERR_HIP;
+}
+
+const char* diffqkv_strerror(int status) {
+  switch (status) {
+    case DIFFQKV_OK: return "ok";
+    case DIFFQKV_ERR_NULL: return "a required pointer is NULL";
+    case DIFFQKV_ERR_SHAPE: return "invalid shape, length or head width";
+    case DIFFQKV_ERR_HEADS: return "head counts must divide n_q and one of n_k, n_v must divide the other";
+    case DIFFQKV_ERR_ALIGN: return "pointer or stride breaks 16-byte row alignment";
+    case DIFFQKV_ERR_WORKSPACE: return "workspace missing or too small";
+    case DIFFQKV_ERR_UNSUPPORTED: return "no kernel for these arguments";
+    case DIFFQKV_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int diffqkv_version(void) { return 100; }
+
+}  // extern "C"

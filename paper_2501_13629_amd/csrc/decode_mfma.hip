@@ -1,0 +1,303 @@
+// Split-decode kernel for bf16 caches on gfx950 matrix cores.
+//
+// One workgroup (4 wavefronts) owns one (sequence, K head, context chunk).  It streams the chunk's
+// K rows once for all g_k = n_q / n_k query rows under that K head, and the rows of each of the
+// R = n_v / n_k V heads under it once for their g_v = n_q / n_v query rows -- the byte count of the
+// cost model in section 3.2 ("KV Cache"): (n_k d_qk + n_v d_v) elements per token.  The head map is
+// the "idx" rule of section 3.2: query row r of the group reads V head  kh * R + r / g_v.
+//
+// Data path (per wavefront, 32 tokens at a time, no LDS in the loop):
+//   S^T = K Q^T      v_mfma_f32_16x16x32_bf16, A = K rows straight from HBM (16 B per lane),
+//                    B = Q^T held in registers.  Result: lane (g, n) holds the scores of query row
+//                    n for tokens 4g..4g+3 of each 16-token block.
+//   online softmax   in that layout: the running maximum is per query row = per lane column, so
+//                    the rescale of the accumulators is lane-local; one cross-lane maximum (two
+//                    shuffles) per 32 tokens.
+//   O^T = V^T P^T    A = V^T: each lane loads 16 B (8 channels) of 8 different tokens and
+//                    transposes the 8x8 block inside its own registers (v_perm_b32), giving the
+//                    8 tokens of one channel per register quad; B = P^T is the softmax output as
+//                    it stands, masked to the query rows of the V head being streamed, so all V
+//                    heads accumulate into one 16 x d_v accumulator.
+// Every global load is 16 B (d_v = 128) or 8 B (d_v = 64) per lane with each 16-lane group reading
+// one contiguous row segment.
+//
+// The 4 wavefronts take interleaved 32-token sub-tiles of each 128-token tile and merge their
+// running (max, sum, accumulator) through LDS at the end of the chunk.  The result is written as a
+// normalised partial output with its base-2 log-sum-exp, or as the final row when there is a
+// single split.
+#include "kernels.h"
+
+namespace diffqkv {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int kSub = 32;             // tokens per wavefront step
+constexpr int kTile = kWaves * kSub; // tokens per workgroup step
+
+// CW bf16 channels (CW * 2 bytes) from a 16-byte-aligned (CW = 8) or 8-byte-aligned (CW = 4) address
+template <int CW>
+struct ChunkLoad;
+template <>
+struct ChunkLoad<8> {
+  static constexpr int kWords = 4;
+  typedef u32x4 vec;
+};
+template <>
+struct ChunkLoad<4> {
+  static constexpr int kWords = 2;
+  typedef u32x2 vec;
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 x = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+template <int DQK, int DV, bool PAGED>
+__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
+  constexpr int KK = DQK / 32;  // k-steps of the score product
+  constexpr int CW = DV / 16;   // channels per lane in the V product
+  constexpr int VW = ChunkLoad<CW>::kWords;
+  typedef typename ChunkLoad<CW>::vec vvec;
+
+  __shared__ float lds_ml[2][kWaves][16];
+  __shared__ float lds_o[kWaves][16][DV + 4];
+
+  const int split = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, n = lane & 15;
+
+  const int G = p.G;                 // query rows under this K head (<= 16)
+  const int R = p.n_v / p.n_k;       // V heads under this K head
+  const int g_v = G / R;             // query rows per V head
+  const int h0 = kh * G;
+
+  int Tb = p.seqlens ? p.seqlens[b] : p.T;
+  Tb = Tb < p.T ? Tb : p.T;
+  const int c0 = split * p.chunk;
+  if (c0 >= Tb) {
+    if (p.num_splits == 1) {  // empty sequence and no combine pass: zeros, lse = -inf
+      uint16_t* out = (uint16_t*)p.out + ((int64_t)b * p.n_q + h0) * DV;
+      for (int o = tid; o < G * DV; o += kThreads) out[o] = 0;
+      if (p.lse_out && tid < G) p.lse_out[(int64_t)b * p.n_q + h0 + tid] = -INFINITY;
+    }
+    return;
+  }
+  const int c1 = (c0 + p.chunk < Tb) ? c0 + p.chunk : Tb;
+  const int last = c1 - 1;
+
+  const uint16_t* kbase = (const uint16_t*)p.k + (int64_t)kh * p.k_sh;
+  const uint16_t* vbase = (const uint16_t*)p.v + (int64_t)(kh * R) * p.v_sh;
+  if (!PAGED) {
+    kbase += (int64_t)b * p.k_sb;
+    vbase += (int64_t)b * p.v_sb;
+  }
+  const int32_t* bt = PAGED ? p.block_table + (int64_t)b * p.max_pages : nullptr;
+
+  // Q^T as the B operand: lane (g, n) holds channels 32 kk + 8 g .. + 7 of query row n.
+  bf16x8 qf[KK];
+  {
+    const uint16_t* qrow = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h0 + (n < G ? n : 0)) * DQK;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      u32x4 w = *(const u32x4*)(qrow + kk * 32 + g * 8);
+      if (n >= G) w = u32x4{0u, 0u, 0u, 0u};
+      qf[kk] = __builtin_bit_cast(bf16x8, w);
+    }
+  }
+
+  f32x4 acc[CW];
+#pragma unroll
+  for (int c = 0; c < CW; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY;  // running maximum of query row n (same in the 4 lanes of a column)
+  float l_run = 0.f;        // this lane's share of the running sum
+
+  for (int ts = c0 + wave * kSub; ts < c1; ts += kTile) {
+    // Two 16-token blocks.  A block that starts beyond the chunk is redirected to the block that
+    // holds the last live token, and rows beyond the last live token to that token: every address
+    // stays inside live cache rows, and the duplicates are masked out of the softmax below.
+    int64_t koff[2], voff[2];
+    int bstart[2];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      int s0 = ts + 16 * blk;
+      int lim = last & ~15;
+      s0 = s0 < lim ? s0 : lim;
+      bstart[blk] = s0;
+      if (PAGED) {
+        int page = bt[s0 / p.page_size];
+        int slot = s0 % p.page_size;
+        koff[blk] = (int64_t)page * p.k_sb + (int64_t)slot * p.k_st;
+        voff[blk] = (int64_t)page * p.v_sb + (int64_t)slot * p.v_st;
+      } else {
+        koff[blk] = (int64_t)s0 * p.k_st;
+        voff[blk] = (int64_t)s0 * p.v_st;
+      }
+    }
+
+    // ---- S^T = K Q^T -----------------------------------------------------------------------------
+    f32x4 sacc[2];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      int r = n;  // row of the block this lane supplies (M index of the A operand)
+      int maxr = last - bstart[blk];
+      r = r < maxr ? r : maxr;
+      const uint16_t* krow = kbase + koff[blk] + (int64_t)r * p.k_st + g * 8;
+      u32x4 kw[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kw[kk] = *(const u32x4*)(krow + kk * 32);
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kw[kk]), qf[kk], s, 0, 0, 0);
+      sacc[blk] = s;
+    }
+
+    // ---- online softmax; lane (g, n): tokens ts + 16 blk + 4 g + x of query row n ---------------
+    float sv[8];
+    float m_tile = -INFINITY;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        int tok = ts + 16 * blk + 4 * g + x;
+        float s = sacc[blk][x] * p.scale_log2;
+        s = tok < c1 ? s : -INFINITY;
+        sv[blk * 4 + x] = s;
+        m_tile = fmaxf(m_tile, s);
+      }
+    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16, 64));
+    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+    const float m_new = fmaxf(m_run, m_tile);  // finite: token ts is live
+    const float fac = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    uint32_t pw[4];  // P^T as the B operand: k-slots 0..3 = block 0, 4..7 = block 1
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float p0 = __builtin_amdgcn_exp2f(sv[2 * i] - m_new);
+      float p1 = __builtin_amdgcn_exp2f(sv[2 * i + 1] - m_new);
+      uint32_t w = pack_bf16x2(p0, p1);
+      pw[i] = w;
+      // the sum runs over the rounded weights, so that they sum to one as used
+      psum += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
+    }
+    l_run = l_run * fac + psum;
+#pragma unroll
+    for (int c = 0; c < CW; ++c) acc[c] *= fac;
+
+    // ---- O^T += V^T P^T, one V head after another ---------------------------------------------
+    for (int vv = 0; vv < R; ++vv) {
+      const uint16_t* vhead = vbase + (int64_t)vv * p.v_sh + n * CW;
+      vvec vr[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int blk = e >> 2;
+        int r = 4 * g + (e & 3);
+        int maxr = last - bstart[blk];
+        r = r < maxr ? r : maxr;
+        vr[e] = *(const vvec*)(vhead + voff[blk] + (int64_t)r * p.v_st);
+      }
+      const bool mine = (n / g_v) == vv;
+      u32x4 pb = {mine ? pw[0] : 0u, mine ? pw[1] : 0u, mine ? pw[2] : 0u, mine ? pw[3] : 0u};
+#pragma unroll
+      for (int c = 0; c < CW; ++c) {
+        // channel c of the lane's chunk: word c/2, low or high half; gather the 8 tokens
+        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 a;
+        a[0] = __builtin_amdgcn_perm(vr[1][c >> 1], vr[0][c >> 1], sel);
+        a[1] = __builtin_amdgcn_perm(vr[3][c >> 1], vr[2][c >> 1], sel);
+        a[2] = __builtin_amdgcn_perm(vr[5][c >> 1], vr[4][c >> 1], sel);
+        a[3] = __builtin_amdgcn_perm(vr[7][c >> 1], vr[6][c >> 1], sel);
+        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                         __builtin_bit_cast(bf16x8, pb), acc[c], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- merge the 4 wavefronts --------------------------------------------------------------------
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (g == 0) {
+    lds_ml[0][wave][n] = m_run;
+    lds_ml[1][wave][n] = l_run;
+  }
+  __syncthreads();
+  float m_all = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, lds_ml[0][w][n]);
+  // a wavefront that saw no token has m = -inf, l = 0, acc = 0: weight 0
+  const float wgt = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_all);
+  // lane (g, n), acc[c][x]: query row n, channel (4 g + x) * CW + c
+#pragma unroll
+  for (int c = 0; c < CW; ++c)
+#pragma unroll
+    for (int x = 0; x < 4; ++x) lds_o[wave][n][(4 * g + x) * CW + c] = acc[c][x] * wgt;
+  __syncthreads();
+
+  for (int o = tid; o < G * DV; o += kThreads) {
+    const int r = o / DV, e = o % DV;
+    float l_all = 0.f, mm = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, lds_ml[0][w][r]);
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      float mw = lds_ml[0][w][r];
+      l_all += (mw == -INFINITY) ? 0.f : lds_ml[1][w][r] * __builtin_amdgcn_exp2f(mw - mm);
+    }
+    float val = (lds_o[0][r][e] + lds_o[1][r][e]) + (lds_o[2][r][e] + lds_o[3][r][e]);
+    val /= l_all;
+    const int64_t row = (int64_t)b * p.n_q + h0 + r;
+    if (p.num_splits == 1) {
+      ((uint16_t*)p.out)[row * DV + e] = float_to_bf16_bits(val);
+      if (e == 0 && p.lse_out) p.lse_out[row] = (mm + log2f(l_all)) * kLn2;
+    } else {
+      p.o_part[(row * p.num_splits + split) * DV + e] = val;
+      if (e == 0) p.lse_part[row * p.num_splits + split] = mm + log2f(l_all);
+    }
+  }
+}
+
+template <int DQK, int DV>
+hipError_t launch_dims(const DecodeParams& p, bool paged, hipStream_t s) {
+  dim3 grid(p.num_splits, p.n_k, p.B), block(kThreads);
+  if (paged)
+    decode_mfma_kernel<DQK, DV, true><<<grid, block, 0, s>>>(p);
+  else
+    decode_mfma_kernel<DQK, DV, false><<<grid, block, 0, s>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// bf16, K the coarser side, at most 16 query rows per K head, head widths 64 or 128.
+bool decode_mfma_supported(const DecodeParams& p, int dtype) {
+  if (dtype != 1) return false;
+  if (p.n_k > p.n_v || p.n_v % p.n_k != 0) return false;
+  if (p.n_q / p.n_k > 16) return false;
+  const bool dq = (p.d_qk == 64 || p.d_qk == 128), dv = (p.d_v == 64 || p.d_v == 128);
+  if (!dq || !dv) return false;
+  if (p.block_table && (p.page_size % 16 != 0)) return false;
+  return true;
+}
+
+hipError_t launch_decode_mfma(const DecodeParams& p, bool paged, hipStream_t s) {
+  if (p.B == 0) return hipSuccess;
+  if (p.d_qk == 128 && p.d_v == 128) return launch_dims<128, 128>(p, paged, s);
+  if (p.d_qk == 64 && p.d_v == 64) return launch_dims<64, 64>(p, paged, s);
+  if (p.d_qk == 64 && p.d_v == 128) return launch_dims<64, 128>(p, paged, s);
+  return launch_dims<128, 64>(p, paged, s);
+}
+
+}  // namespace diffqkv

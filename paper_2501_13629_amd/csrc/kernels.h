@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of libdiffqkv (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace diffqkv {
+
+// Everything a decode launch needs; filled by the boundary after validation.
+struct DecodeParams {
+  const void* q;    // [B, n_q, d_qk]
+  const void* k;    // contiguous cache or page pool
+  const void* v;
+  int64_t k_sb, k_sh, k_st;  // batch (or page) / head / token strides, in elements
+  int64_t v_sb, v_sh, v_st;
+  const int32_t* seqlens;      // device [B] or nullptr
+  const int32_t* block_table;  // device [B, max_pages], paged only
+  int32_t max_pages, page_size;
+  int32_t T;  // uniform length, or upper bound when seqlens is given
+  int32_t B, n_q, n_k, n_v, d_qk, d_v;
+  int32_t n_groups;  // workgroup-owning heads per sequence: min(n_k, n_v)
+  int32_t G;         // query rows per group: n_q / n_groups
+  int32_t chunk;     // tokens per context split
+  int32_t num_splits;
+  float scale_log2;  // softmax scale * log2(e): scores live in the base-2 domain
+  float* o_part;     // [B, n_q, num_splits, d_v] normalised partial outputs
+  float* lse_part;   // [B, n_q, num_splits]      base-2 log-sum-exp of each split
+  void* out;         // [B, n_q, d_v]
+  float* lse_out;    // [B, n_q] or nullptr (natural log)
+};
+
+struct PrefillParams {
+  const void* q;  // [B, n_q, S_q, d_qk]
+  const void* k;  // [B, n_k, S_k, d_qk]
+  const void* v;  // [B, n_v, S_k, d_v]
+  void* out;      // [B, n_q, S_q, d_v]
+  float* lse_out; // [B, n_q, S_q] or nullptr
+  int32_t B, n_q, n_k, n_v, d_qk, d_v, S_q, S_k, causal;
+  float scale_log2;
+};
+
+// dtype: 0 = fp32, 1 = bf16 (diffqkv_dtype).  All return a hipError_t from the launch.
+hipError_t launch_decode_generic(const DecodeParams& p, int dtype, bool paged, hipStream_t s);
+bool decode_mfma_supported(const DecodeParams& p, int dtype);
+hipError_t launch_decode_mfma(const DecodeParams& p, bool paged, hipStream_t s);
+hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s);
+hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t s);
+bool prefill_mfma_supported(const PrefillParams& p, int dtype);
+hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s);
+hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
+
+// ---- small device helpers -------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// round-to-nearest-even fp32 -> bf16 bits (NaN stays NaN)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float load_as_float(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float load_as_float(const uint16_t* p, int64_t i) {
+  return bf16_bits_to_float(p[i]);
+}
+__device__ __forceinline__ void store_from_float(float* p, int64_t i, float x) { p[i] = x; }
+__device__ __forceinline__ void store_from_float(uint16_t* p, int64_t i, float x) {
+  p[i] = float_to_bf16_bits(x);
+}
+
+constexpr float kLn2 = 0.69314718055994530942f;
+constexpr float kLog2e = 1.44269504088896340736f;
+
+}  // namespace diffqkv

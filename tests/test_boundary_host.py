@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares, and
+its argument validation returns the documented status codes without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2501_13629_amd import binding
+from paper_2501_13629_amd.binding import Shape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+OK, E_NULL, E_SHAPE, E_HEADS, E_ALIGN, E_WS = 0, -1, -2, -3, -4, -5
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not binding.LIB_PATH.exists():
+        from paper_2501_13629_amd import build
+
+        build.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "diffqkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(diffqkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 9
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_version_and_strerror(lib):
+    assert lib.diffqkv_version() >= 100
+    assert lib.diffqkv_strerror(0) == b"ok"
+    for code in range(-7, 0):
+        assert len(lib.diffqkv_strerror(code)) > 3
+
+
+def shape(B=2, n_q=8, n_k=2, n_v=4, d_qk=64, d_v=64, dtype=1, scale=0.0):
+    return Shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, scale)
+
+
+def decode(lib, s, q=0x1000, k=0x2000, v=0x3000, ks=(8192, 4096, 64), vs=(8192, 4096, 64), T=64, out=0x4000,
+           ws=0x5000, ws_bytes=1 << 30):
+    vp = ctypes.c_void_p
+    return lib.diffqkv_decode(ctypes.byref(s), vp(q), vp(k), vp(v), *ks, *vs, None, T, vp(out), None, vp(ws),
+                              ws_bytes, None)
+
+
+def test_decode_validation_codes(lib):
+    vp = ctypes.c_void_p
+    assert lib.diffqkv_decode(None, vp(16), vp(16), vp(16), 64, 64, 64, 64, 64, 64, None, 1, vp(16), None, None, 0,
+                              None) == E_NULL
+    assert decode(lib, shape(n_q=0)) == E_SHAPE
+    assert decode(lib, shape(d_qk=60)) == E_SHAPE
+    assert decode(lib, shape(d_v=512)) == E_SHAPE
+    assert decode(lib, shape(dtype=7)) == E_SHAPE
+    assert decode(lib, shape(scale=-1.0)) == E_SHAPE
+    assert decode(lib, shape(), T=-1) == E_SHAPE
+    assert decode(lib, shape(n_q=8, n_k=3)) == E_HEADS
+    assert decode(lib, shape(n_q=12, n_k=4, n_v=6)) == E_HEADS  # neither divides the other
+    assert decode(lib, shape(), q=0) == E_NULL
+    assert decode(lib, shape(), out=0) == E_NULL
+    assert decode(lib, shape(), k=0x2004) == E_ALIGN
+    assert decode(lib, shape(), ks=(8192, 4096, 60)) == E_ALIGN
+    assert decode(lib, shape(), ks=(8192, 4096, 32)) == E_SHAPE  # rows would overlap
+    # a context long enough to need splits needs a workspace
+    s = shape(B=1)
+    need = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 1 << 16)
+    assert need > 0
+    assert decode(lib, s, T=1 << 16, ws=0) == E_WS
+    assert decode(lib, s, T=1 << 16, ws_bytes=need - 1) == E_WS
+    # an empty batch is a valid no-op and launches nothing
+    assert decode(lib, shape(B=0), q=0, k=0, v=0, out=0, ws=0, ws_bytes=0) == OK
+
+
+def test_paged_and_prefill_validation_codes(lib):
+    vp = ctypes.c_void_p
+    s = shape()
+
+    def paged(max_pages=4, page=16, seqlens=0x6000, bt=0x7000, kst=(4096, 1024, 64)):
+        return lib.diffqkv_decode_paged(ctypes.byref(s), vp(0x1000), vp(0x2000), vp(0x3000), *kst, 4096, 1024, 64,
+                                        vp(bt), max_pages, page, vp(seqlens), vp(0x4000), None, vp(0x5000),
+                                        1 << 30, None)
+
+    assert paged(page=0) == E_SHAPE
+    assert paged(max_pages=-1) == E_SHAPE
+    assert paged(max_pages=1 << 30, page=16) == E_SHAPE
+    assert paged(seqlens=0) == E_NULL
+    assert paged(bt=0) == E_NULL
+    assert paged(kst=(4096, 1024, 68)) == E_ALIGN
+
+    def prefill(S_q=16, S_k=16, causal=1, q=0x1000):
+        return lib.diffqkv_prefill(ctypes.byref(s), vp(q), vp(0x2000), vp(0x3000), S_q, S_k, causal, vp(0x4000),
+                                   None, None, 0, None)
+
+    assert prefill(S_q=0) == E_SHAPE
+    assert prefill(S_q=32, S_k=16) == E_SHAPE
+    assert prefill(q=0) == E_NULL
+    assert prefill(q=0x1008) == E_ALIGN
+
+
+def test_split_plan_is_a_function_of_shapes(lib):
+    s = shape(B=8, n_q=32, n_k=2, n_v=8, d_qk=128, d_v=128)
+    a = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
+    b = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
+    assert a == b and a % 256 == 0 and a > 0
+    # short contexts run in a single pass and need no workspace
+    assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 128) == 0
+    # the knob changes the plan; resetting restores it
+    binding.diffqkv_set_tuning(decode_chunk_tokens=2048)
+    c = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
+    binding.diffqkv_set_tuning()
+    assert c != a and lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == a
+    assert c == 8 * 32 * 16 * 129 * 4
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    q = torch.zeros(1, 4, 64)
+    k = torch.zeros(1, 1, 8, 64)
+    v = torch.zeros(1, 2, 8, 64)
+    with pytest.raises(RuntimeError, match="GPU only"):
+        binding.diffqkv_decode(q, k, v)
