@@ -90,8 +90,9 @@ void diffqkv_set_tuning(const diffqkv_tuning* t /* host; NULL resets */);
  *            T_b is clamped to it.  T >= 0.
  *   out      [B, n_q, d_v]   dtype of the inputs
  *   lse_out  float [B, n_q] natural-log sum of exp of the scaled scores, or NULL
- *   workspace/workspace_bytes  at least diffqkv_decode_workspace_bytes(shape, T) bytes, 256-byte
- *            aligned; holds the per-split partial outputs and their log-sum-exps
+ *   workspace/workspace_bytes  at least diffqkv_decode_workspace_bytes(shape, T) bytes (a figure
+ *            that covers the call with and without seqlens), 16-byte aligned; holds the per-split
+ *            partial outputs and their log-sum-exps
  */
 size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape /* host */, int32_t max_T);
 int diffqkv_decode(const diffqkv_shape* shape /* host */, const void* q, const void* k_cache,

@@ -13,11 +13,17 @@ namespace {
 diffqkv_tuning g_tuning = {};
 hipEvent_t g_split_event = nullptr;
 
-constexpr int kComputeUnits = 256;  // MI355X; the split plan is a pure function of the shapes
-constexpr int kTargetWorkgroups = 4 * kComputeUnits;
+// Split plan, a pure function of the shapes.  Measured on MI355X: the decode kernel streams fastest
+// when the whole context fits one round of workgroups, one per compute unit, each as long as
+// possible (every extra round exposes a prologue and an epilogue with no loads in flight).
+constexpr int kComputeUnits = 256;
+constexpr int kTargetWorkgroups = kComputeUnits;
 constexpr int kChunkQuantum = 128;  // one workgroup step of the decode kernels
 constexpr int kMinChunk = 256;
-constexpr int kMaxChunk = 1024;
+constexpr int kMaxChunk = 8192;
+// With per-sequence lengths the work per (sequence, head) is uneven and unknown on the host:
+// shorter chunks let the hardware dispatcher balance it.
+constexpr int kMaxChunkRagged = 2048;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int dtype) { return dtype == DIFFQKV_F32 ? 4 : 2; }
@@ -42,7 +48,7 @@ float scale_log2(const diffqkv_shape* s) {
 }
 
 // Context split: a pure function of the shapes so that results are repeatable bit for bit.
-void plan_decode(const diffqkv_shape* s, int32_t max_T, int32_t* chunk, int32_t* num_splits) {
+void plan_decode(const diffqkv_shape* s, int32_t max_T, bool ragged, int32_t* chunk, int32_t* num_splits) {
   int c;
   if (g_tuning.decode_chunk_tokens > 0) {
     c = (g_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
@@ -51,7 +57,8 @@ void plan_decode(const diffqkv_shape* s, int32_t max_T, int32_t* chunk, int32_t*
     const int64_t total = (int64_t)max_T * groups;
     int64_t per = (total + kTargetWorkgroups - 1) / kTargetWorkgroups;
     per = (per + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
-    c = (int)(per < kMinChunk ? kMinChunk : (per > kMaxChunk ? kMaxChunk : per));
+    const int hi = ragged ? kMaxChunkRagged : kMaxChunk;
+    c = (int)(per < kMinChunk ? kMinChunk : (per > hi ? hi : per));
   }
   *chunk = c;
   int n = (int)(((int64_t)max_T + c - 1) / c);
@@ -67,7 +74,7 @@ size_t workspace_for(const diffqkv_shape* s, int32_t num_splits) {
 
 int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* workspace,
                size_t workspace_bytes, hipStream_t stream) {
-  plan_decode(s, p.T, &p.chunk, &p.num_splits);
+  plan_decode(s, p.T, p.seqlens != nullptr, &p.chunk, &p.num_splits);
   const size_t need = workspace_for(s, p.num_splits);
   if (need) {
     if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
@@ -114,8 +121,9 @@ void diffqkv_set_split_event(void* hip_event) { g_split_event = (hipEvent_t)hip_
 
 size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape, int32_t max_T) {
   if (check_shape(shape) != DIFFQKV_OK || max_T < 0) return 0;
+  // the ragged plan never has fewer splits than the uniform one: its size covers both
   int32_t chunk, splits;
-  plan_decode(shape, max_T, &chunk, &splits);
+  plan_decode(shape, max_T, true, &chunk, &splits);
   return workspace_for(shape, splits);
 }
 

@@ -181,32 +181,69 @@ __global__ __launch_bounds__(kThreads) void decode_generic_kernel(DecodeParams p
 // One workgroup per (sequence, query head): merges the live splits of that row.
 //   lse = log2 sum_s 2^{lse_s},   out = sum_s 2^{lse_s - lse} o_s
 // Sequences of length zero get out = 0, lse = -inf.  Only launched when num_splits > 1.
+// Threads are laid out as (split lane, channel quad): each thread sums every nsl-th split of four
+// channels with independent 16-byte loads, then the split lanes are added in a fixed order in LDS.
+constexpr int kCombineThreads = 256;
+
 template <typename T>
-__global__ __launch_bounds__(128) void combine_kernel(DecodeParams p) {
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(DecodeParams p) {
+  __shared__ float red[kCombineThreads * 4];
+  __shared__ float stat[2];
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   int Tb = p.seqlens ? p.seqlens[b] : p.T;
   Tb = Tb < p.T ? Tb : p.T;
   const int64_t row = (int64_t)b * p.n_q + h;
   T* out = (T*)p.out + row * p.d_v;
   if (Tb <= 0) {
-    for (int e = tid; e < p.d_v; e += 128) store_from_float(out, e, 0.f);
+    for (int e = tid; e < p.d_v; e += kCombineThreads) store_from_float(out, e, 0.f);
     if (tid == 0 && p.lse_out) p.lse_out[row] = -INFINITY;
     return;
   }
   const int live = (Tb + p.chunk - 1) / p.chunk;
   const float* lp = p.lse_part + row * p.num_splits;
   const float* op = p.o_part + row * p.num_splits * p.d_v;
-  float m = -INFINITY;
-  for (int s = 0; s < live; ++s) m = fmaxf(m, lp[s]);
-  float l = 0.f;
-  for (int s = 0; s < live; ++s) l += exp2f(lp[s] - m);
-  const float inv = 1.f / l;
-  for (int e = tid; e < p.d_v; e += 128) {
-    float a = 0.f;
-    for (int s = 0; s < live; ++s) a = fmaf(exp2f(lp[s] - m) * inv, op[(int64_t)s * p.d_v + e], a);
-    store_from_float(out, e, a);
+
+  // log-sum-exp of the live splits, by the first wavefront
+  if (tid < 64) {
+    float m = -INFINITY;
+    for (int s = tid; s < live; s += 64) m = fmaxf(m, lp[s]);
+    m = wave_max(m);
+    float l = 0.f;
+    for (int s = tid; s < live; s += 64) l += exp2f(lp[s] - m);
+    l = wave_sum(l);
+    if (tid == 0) {
+      stat[0] = m;
+      stat[1] = l;
+    }
   }
-  if (tid == 0 && p.lse_out) p.lse_out[row] = (m + log2f(l)) * kLn2;
+  __syncthreads();
+  const float m = stat[0], inv = 1.f / stat[1];
+
+  const int nq = p.d_v / 4;               // channel quads
+  const int nsl = kCombineThreads / nq;   // split lanes
+  const int sl = tid / nq, cq = tid % nq;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (sl < nsl) {
+    for (int s = sl; s < live; s += nsl) {
+      const float w = exp2f(lp[s] - m) * inv;
+      const float4 x = *(const float4*)(op + (int64_t)s * p.d_v + cq * 4);
+      a.x = fmaf(w, x.x, a.x);
+      a.y = fmaf(w, x.y, a.y);
+      a.z = fmaf(w, x.z, a.z);
+      a.w = fmaf(w, x.w, a.w);
+    }
+  }
+  red[tid * 4 + 0] = a.x;
+  red[tid * 4 + 1] = a.y;
+  red[tid * 4 + 2] = a.z;
+  red[tid * 4 + 3] = a.w;
+  __syncthreads();
+  for (int e = tid; e < p.d_v; e += kCombineThreads) {
+    float v = 0.f;
+    for (int j = 0; j < nsl; ++j) v += red[(j * nq + e / 4) * 4 + (e & 3)];
+    store_from_float(out, e, v);
+  }
+  if (tid == 0 && p.lse_out) p.lse_out[row] = (m + log2f(stat[1])) * kLn2;
 }
 
 }  // namespace
@@ -233,7 +270,7 @@ hipError_t launch_decode_generic(const DecodeParams& p, int dtype, bool paged, h
 
 hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
-  dim3 grid(p.n_q, p.B), block(128);
+  dim3 grid(p.n_q, p.B), block(kCombineThreads);
   if (dtype == 0)
     combine_kernel<float><<<grid, block, 0, s>>>(p);
   else

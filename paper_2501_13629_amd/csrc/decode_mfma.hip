@@ -25,6 +25,8 @@
 // running (max, sum, accumulator) through LDS at the end of the chunk.  The result is written as a
 // normalised partial output with its base-2 log-sum-exp, or as the final row when there is a
 // single split.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace diffqkv {
@@ -62,11 +64,35 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
-template <int DQK, int DV, bool PAGED>
-__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
+// Raw buffer resource over [base, base + 2 GiB): lets a load take a wavefront-uniform byte offset
+// in a scalar register on top of the per-lane offset, so the loop carries no per-lane address
+// arithmetic.  Every offset used below addresses a live cache row (checked on the host against the
+// 2 GiB window; rows past the end of a sequence are redirected, never read).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+// Cache rows are read exactly once: the loads carry the non-temporal hint (streaming, no reuse).
+constexpr int kNonTemporal = 2;
+template <int CW>
+__device__ __forceinline__ typename ChunkLoad<CW>::vec buffer_load_chunk(rsrc_t r, int voff, int soff);
+template <>
+__device__ __forceinline__ u32x4 buffer_load_chunk<8>(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, kNonTemporal);
+}
+template <>
+__device__ __forceinline__ u32x2 buffer_load_chunk<4>(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, kNonTemporal);
+}
+
+// RT: number of V heads per K head when it is one of the unrolled cases (1, 2, 4, 8); then the loop
+// over V heads is unrolled and software-pipelined: while the matrix cores work on one unit (the K
+// rows of a sub-tile, or the rows of one V head), the loads of the next unit are already in flight
+// into a second set of registers.  RT = 0 takes any ratio with a plain loop.
+template <int DQK, int DV, bool PAGED, int RT>
+__global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p) {
   constexpr int KK = DQK / 32;  // k-steps of the score product
   constexpr int CW = DV / 16;   // channels per lane in the V product
-  constexpr int VW = ChunkLoad<CW>::kWords;
   typedef typename ChunkLoad<CW>::vec vvec;
 
   __shared__ float lds_ml[2][kWaves][16];
@@ -78,9 +104,9 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n = lane & 15;
 
-  const int G = p.G;                 // query rows under this K head (<= 16)
-  const int R = p.n_v / p.n_k;       // V heads under this K head
-  const int g_v = G / R;             // query rows per V head
+  const int G = p.G;                           // query rows under this K head (<= 16)
+  const int R = RT ? RT : p.n_v / p.n_k;       // V heads under this K head
+  const int g_v = G / R;                       // query rows per V head
   const int h0 = kh * G;
 
   int Tb = p.seqlens ? p.seqlens[b] : p.T;
@@ -97,13 +123,15 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
   const int c1 = (c0 + p.chunk < Tb) ? c0 + p.chunk : Tb;
   const int last = c1 - 1;
 
-  const uint16_t* kbase = (const uint16_t*)p.k + (int64_t)kh * p.k_sh;
-  const uint16_t* vbase = (const uint16_t*)p.v + (int64_t)(kh * R) * p.v_sh;
+  // wavefront-uniform bases of this K head and of the first V head under it
+  const uint16_t* khead = (const uint16_t*)p.k + (int64_t)kh * p.k_sh;
+  const uint16_t* vhead = (const uint16_t*)p.v + (int64_t)(kh * R) * p.v_sh;
   if (!PAGED) {
-    kbase += (int64_t)b * p.k_sb;
-    vbase += (int64_t)b * p.v_sb;
+    khead += (int64_t)b * p.k_sb;
+    vhead += (int64_t)b * p.v_sb;
   }
   const int32_t* bt = PAGED ? p.block_table + (int64_t)b * p.max_pages : nullptr;
+  const int k_row_bytes = (int)p.k_st * 2, v_row_bytes = (int)p.v_st * 2, v_head_bytes = (int)p.v_sh * 2;
 
   // Q^T as the B operand: lane (g, n) holds channels 32 kk + 8 g .. + 7 of query row n.
   bf16x8 qf[KK];
@@ -117,78 +145,117 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
     }
   }
 
+  // Where a sub-tile (two 16-token blocks starting at token ts) lives: one buffer resource per
+  // block for K and for V (a block never straddles a page), plus this lane's byte offsets inside
+  // the block.  In a full sub-tile the lane offsets are loop constants: K row n, V rows 4 g + x.
+  // In the last, partial sub-tile of a sequence a block that starts beyond the last live token is
+  // redirected to the block that holds it and a row beyond it to that token, so every address
+  // stays inside live rows; the duplicates are masked out of the softmax.
+  struct SubTile {
+    rsrc_t k[2], v[2];
+  };
+  struct LaneOffsets {
+    int k[2];
+    int v[2][4];
+  };
+  auto block_start = [&](int ts, int blk, bool tail) {
+    int s0 = ts + 16 * blk;
+    if (tail) {
+      const int lim = last & ~15;
+      s0 = s0 < lim ? s0 : lim;
+    }
+    return s0;
+  };
+  auto locate = [&](int ts, bool tail) {
+    SubTile t;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      const int s0 = block_start(ts, blk, tail);
+      int64_t ko, vo;
+      if (PAGED) {
+        const int page = bt[s0 / p.page_size];
+        const int slot = s0 % p.page_size;
+        ko = (int64_t)page * p.k_sb + (int64_t)slot * p.k_st;
+        vo = (int64_t)page * p.v_sb + (int64_t)slot * p.v_st;
+      } else {
+        ko = (int64_t)s0 * p.k_st;
+        vo = (int64_t)s0 * p.v_st;
+      }
+      t.k[blk] = make_rsrc(khead + ko);
+      t.v[blk] = make_rsrc(vhead + vo);
+    }
+    return t;
+  };
+  LaneOffsets full_off;
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk) {
+    full_off.k[blk] = n * k_row_bytes + g * 16;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) full_off.v[blk][x] = (4 * g + x) * v_row_bytes + n * (CW * 2);
+  }
+  auto tail_offsets = [&](int ts) {
+    LaneOffsets o;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      const int maxr = last - block_start(ts, blk, true);
+      o.k[blk] = (n < maxr ? n : maxr) * k_row_bytes + g * 16;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int r = 4 * g + x;
+        o.v[blk][x] = (r < maxr ? r : maxr) * v_row_bytes + n * (CW * 2);
+      }
+    }
+    return o;
+  };
+  auto load_k = [&](const SubTile& t, const LaneOffsets& o, u32x4 (&kw)[2][KK]) {
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        kw[blk][kk] = __builtin_amdgcn_raw_buffer_load_b128(t.k[blk], o.k[blk] + kk * 64, 0, kNonTemporal);
+  };
+  auto load_v = [&](const SubTile& t, const LaneOffsets& o, int vv, vvec (&vr)[8]) {
+    const int head = vv * v_head_bytes;  // wavefront-uniform: travels in a scalar register
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vr[e] = buffer_load_chunk<CW>(t.v[e >> 2], o.v[e >> 2][e & 3], head);
+  };
+
   f32x4 acc[CW];
 #pragma unroll
   for (int c = 0; c < CW; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY;  // running maximum of query row n (same in the 4 lanes of a column)
   float l_run = 0.f;        // this lane's share of the running sum
+  uint32_t pw[4];           // P^T as the B operand: k-slots 0..3 = block 0, 4..7 = block 1
 
-  for (int ts = c0 + wave * kSub; ts < c1; ts += kTile) {
-    // Two 16-token blocks.  A block that starts beyond the chunk is redirected to the block that
-    // holds the last live token, and rows beyond the last live token to that token: every address
-    // stays inside live cache rows, and the duplicates are masked out of the softmax below.
-    int64_t koff[2], voff[2];
-    int bstart[2];
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      int s0 = ts + 16 * blk;
-      int lim = last & ~15;
-      s0 = s0 < lim ? s0 : lim;
-      bstart[blk] = s0;
-      if (PAGED) {
-        int page = bt[s0 / p.page_size];
-        int slot = s0 % p.page_size;
-        koff[blk] = (int64_t)page * p.k_sb + (int64_t)slot * p.k_st;
-        voff[blk] = (int64_t)page * p.v_sb + (int64_t)slot * p.v_st;
-      } else {
-        koff[blk] = (int64_t)s0 * p.k_st;
-        voff[blk] = (int64_t)s0 * p.v_st;
-      }
-    }
-
-    // ---- S^T = K Q^T -----------------------------------------------------------------------------
-    f32x4 sacc[2];
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      int r = n;  // row of the block this lane supplies (M index of the A operand)
-      int maxr = last - bstart[blk];
-      r = r < maxr ? r : maxr;
-      const uint16_t* krow = kbase + koff[blk] + (int64_t)r * p.k_st + g * 8;
-      u32x4 kw[KK];
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kw[kk] = *(const u32x4*)(krow + kk * 32);
-      f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kw[kk]), qf[kk], s, 0, 0, 0);
-      sacc[blk] = s;
-    }
-
-    // ---- online softmax; lane (g, n): tokens ts + 16 blk + 4 g + x of query row n ---------------
+  // S^T = K Q^T, then the online softmax.  Lane (g, n): tokens ts + 16 blk + 4 g + x of row n.
+  auto scores_and_softmax = [&](int ts, const u32x4 (&kw)[2][KK], bool tail) {
     float sv[8];
     float m_tile = -INFINITY;
 #pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
+    for (int blk = 0; blk < 2; ++blk) {
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kw[blk][kk]), qf[kk], s, 0, 0, 0);
 #pragma unroll
       for (int x = 0; x < 4; ++x) {
-        int tok = ts + 16 * blk + 4 * g + x;
-        float s = sacc[blk][x] * p.scale_log2;
-        s = tok < c1 ? s : -INFINITY;
-        sv[blk * 4 + x] = s;
-        m_tile = fmaxf(m_tile, s);
+        float v = s[x] * p.scale_log2;
+        if (tail) v = (ts + 16 * blk + 4 * g + x) < c1 ? v : -INFINITY;
+        sv[blk * 4 + x] = v;
+        m_tile = fmaxf(m_tile, v);
       }
+    }
     m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16, 64));
     m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
     const float m_new = fmaxf(m_run, m_tile);  // finite: token ts is live
     const float fac = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
-    uint32_t pw[4];  // P^T as the B operand: k-slots 0..3 = block 0, 4..7 = block 1
     float psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float p0 = __builtin_amdgcn_exp2f(sv[2 * i] - m_new);
-      float p1 = __builtin_amdgcn_exp2f(sv[2 * i + 1] - m_new);
-      uint32_t w = pack_bf16x2(p0, p1);
+      const float p0 = __builtin_amdgcn_exp2f(sv[2 * i] - m_new);
+      const float p1 = __builtin_amdgcn_exp2f(sv[2 * i + 1] - m_new);
+      const uint32_t w = pack_bf16x2(p0, p1);
       pw[i] = w;
       // the sum runs over the rounded weights, so that they sum to one as used
       psum += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
@@ -196,34 +263,80 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
     l_run = l_run * fac + psum;
 #pragma unroll
     for (int c = 0; c < CW; ++c) acc[c] *= fac;
+  };
 
-    // ---- O^T += V^T P^T, one V head after another ---------------------------------------------
-    for (int vv = 0; vv < R; ++vv) {
-      const uint16_t* vhead = vbase + (int64_t)vv * p.v_sh + n * CW;
-      vvec vr[8];
+  // O^T += V^T P^T for one V head: transpose each lane's 8 tokens x CW channels in registers.
+  auto accumulate_v = [&](int vv, const vvec (&vr)[8]) {
+    const bool mine = (n / g_v) == vv;
+    const u32x4 pb = {mine ? pw[0] : 0u, mine ? pw[1] : 0u, mine ? pw[2] : 0u, mine ? pw[3] : 0u};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int blk = e >> 2;
-        int r = 4 * g + (e & 3);
-        int maxr = last - bstart[blk];
-        r = r < maxr ? r : maxr;
-        vr[e] = *(const vvec*)(vhead + voff[blk] + (int64_t)r * p.v_st);
-      }
-      const bool mine = (n / g_v) == vv;
-      u32x4 pb = {mine ? pw[0] : 0u, mine ? pw[1] : 0u, mine ? pw[2] : 0u, mine ? pw[3] : 0u};
-#pragma unroll
-      for (int c = 0; c < CW; ++c) {
-        // channel c of the lane's chunk: word c/2, low or high half; gather the 8 tokens
-        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-        u32x4 a;
-        a[0] = __builtin_amdgcn_perm(vr[1][c >> 1], vr[0][c >> 1], sel);
-        a[1] = __builtin_amdgcn_perm(vr[3][c >> 1], vr[2][c >> 1], sel);
-        a[2] = __builtin_amdgcn_perm(vr[5][c >> 1], vr[4][c >> 1], sel);
-        a[3] = __builtin_amdgcn_perm(vr[7][c >> 1], vr[6][c >> 1], sel);
-        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                         __builtin_bit_cast(bf16x8, pb), acc[c], 0, 0, 0);
-      }
+    for (int c = 0; c < CW; ++c) {
+      const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 a;
+      a[0] = __builtin_amdgcn_perm(vr[1][c >> 1], vr[0][c >> 1], sel);
+      a[1] = __builtin_amdgcn_perm(vr[3][c >> 1], vr[2][c >> 1], sel);
+      a[2] = __builtin_amdgcn_perm(vr[5][c >> 1], vr[4][c >> 1], sel);
+      a[3] = __builtin_amdgcn_perm(vr[7][c >> 1], vr[6][c >> 1], sel);
+      acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, pb), acc[c], 0, 0, 0);
     }
+  };
+
+  // A sub-tile with no overlap of loads and arithmetic: the partial last sub-tile, and RT = 0.
+  auto plain_sub_tile = [&](int ts, bool tail) {
+    const SubTile t = locate(ts, tail);
+    const LaneOffsets o = tail ? tail_offsets(ts) : full_off;
+    u32x4 kw[2][KK];
+    load_k(t, o, kw);
+    scores_and_softmax(ts, kw, tail);
+    for (int vv = 0; vv < R; ++vv) {
+      vvec vr[8];
+      load_v(t, o, vv, vr);
+      accumulate_v(vv, vr);
+    }
+  };
+
+  int ts = c0 + wave * kSub;
+  if (RT) {
+    if (ts + kSub <= c1) {  // at least one full sub-tile
+      u32x4 kw[2][KK];
+      vvec va[8], vb[8];
+      SubTile cur = locate(ts, false);
+      load_k(cur, full_off, kw);
+      // MORE is a compile-time flag (a K prefetch for the next full sub-tile follows), so that the
+      // number of loads in flight at every wait is known statically.
+      auto sub_tile = [&](auto more_tag) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        load_v(cur, full_off, 0, va);
+        scores_and_softmax(ts, kw, false);
+        SubTile nxt = cur;
+        if (MORE) nxt = locate(ts + kTile, false);
+#pragma unroll
+        for (int vv = 0; vv < RT; ++vv) {
+          // put the next unit's loads in flight, then consume the current V head
+          if (vv + 1 < RT) {
+            if (vv & 1)
+              load_v(cur, full_off, vv + 1, va);
+            else
+              load_v(cur, full_off, vv + 1, vb);
+          } else if (MORE) {
+            load_k(nxt, full_off, kw);
+          }
+          if (vv & 1)
+            accumulate_v(vv, vb);
+          else
+            accumulate_v(vv, va);
+        }
+        cur = nxt;
+        ts += kTile;
+      };
+      while (ts + kTile + kSub <= c1) sub_tile(std::true_type{});
+      sub_tile(std::false_type{});
+    }
+    if (ts < c1) plain_sub_tile(ts, true);
+  } else {
+    for (; ts + kSub <= c1; ts += kTile) plain_sub_tile(ts, false);
+    if (ts < c1) plain_sub_tile(ts, true);
   }
 
   // ---- merge the 4 wavefronts --------------------------------------------------------------------
@@ -269,14 +382,25 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(DecodeParams p) {
   }
 }
 
-template <int DQK, int DV>
-hipError_t launch_dims(const DecodeParams& p, bool paged, hipStream_t s) {
+template <int DQK, int DV, int RT>
+hipError_t launch_ratio(const DecodeParams& p, bool paged, hipStream_t s) {
   dim3 grid(p.num_splits, p.n_k, p.B), block(kThreads);
   if (paged)
-    decode_mfma_kernel<DQK, DV, true><<<grid, block, 0, s>>>(p);
+    decode_mfma_kernel<DQK, DV, true, RT><<<grid, block, 0, s>>>(p);
   else
-    decode_mfma_kernel<DQK, DV, false><<<grid, block, 0, s>>>(p);
+    decode_mfma_kernel<DQK, DV, false, RT><<<grid, block, 0, s>>>(p);
   return hipGetLastError();
+}
+
+template <int DQK, int DV>
+hipError_t launch_dims(const DecodeParams& p, bool paged, hipStream_t s) {
+  switch (p.n_v / p.n_k) {
+    case 1: return launch_ratio<DQK, DV, 1>(p, paged, s);
+    case 2: return launch_ratio<DQK, DV, 2>(p, paged, s);
+    case 4: return launch_ratio<DQK, DV, 4>(p, paged, s);
+    case 8: return launch_ratio<DQK, DV, 8>(p, paged, s);
+    default: return launch_ratio<DQK, DV, 0>(p, paged, s);
+  }
 }
 
 }  // namespace
@@ -289,6 +413,10 @@ bool decode_mfma_supported(const DecodeParams& p, int dtype) {
   const bool dq = (p.d_qk == 64 || p.d_qk == 128), dv = (p.d_v == 64 || p.d_v == 128);
   if (!dq || !dv) return false;
   if (p.block_table && (p.page_size % 16 != 0)) return false;
+  // every byte offset inside a 16-token block, V head offset included, must fit the 2 GiB window
+  const int64_t R = p.n_v / p.n_k;
+  if (16 * p.k_st * 2 + 512 >= (1ll << 31)) return false;
+  if ((R * p.v_sh + 16 * p.v_st) * 2 + 512 >= (1ll << 31)) return false;
   return true;
 }
 

@@ -116,11 +116,11 @@ def test_split_plan_is_a_function_of_shapes(lib):
     # short contexts run in a single pass and need no workspace
     assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 128) == 0
     # the knob changes the plan; resetting restores it
-    binding.diffqkv_set_tuning(decode_chunk_tokens=2048)
+    binding.diffqkv_set_tuning(decode_chunk_tokens=512)
     c = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
     binding.diffqkv_set_tuning()
     assert c != a and lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == a
-    assert c == 8 * 32 * 16 * 129 * 4
+    assert c == 8 * 32 * 64 * 129 * 4
 
 
 def test_binding_refuses_cpu_tensors():
