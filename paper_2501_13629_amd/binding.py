@@ -33,7 +33,7 @@ class Shape(ctypes.Structure):
 
 class Tuning(ctypes.Structure):
     _fields_ = [("decode_chunk_tokens", ctypes.c_int32), ("force_generic", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 6)]
+                ("prefill_query_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
 
 
 class DiffQKVError(RuntimeError):
@@ -114,8 +114,8 @@ def _shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, scale) -> Shape:
     return Shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, 0.0 if scale is None else float(scale))
 
 
-def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False):
-    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0)
+def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False, prefill_query_blocks: int = 0):
+    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0, int(prefill_query_blocks))
     load_library().diffqkv_set_tuning(ctypes.byref(t))
 
 
