@@ -73,7 +73,7 @@ typedef struct {
 typedef struct {
   int32_t decode_chunk_tokens; /* tokens per context split (multiple of 128)                      */
   int32_t force_generic;       /* 1: always take the portable kernels instead of the MFMA ones    */
-  int32_t prefill_query_blocks; /* 32-row query blocks per wavefront in the MFMA prefill: 1 or 2  */
+  int32_t prefill_waves;       /* wavefronts per workgroup in the MFMA prefill: 4 or 8           */
   int32_t reserved[5];
 } diffqkv_tuning;
 void diffqkv_set_tuning(const diffqkv_tuning* t /* host; NULL resets */);

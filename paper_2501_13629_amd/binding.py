@@ -9,6 +9,7 @@ Functions carry the names of the C entry points in ``include/diffqkv.h``.
 from __future__ import annotations
 
 import ctypes
+import os
 from pathlib import Path
 
 import torch
@@ -33,7 +34,7 @@ class Shape(ctypes.Structure):
 
 class Tuning(ctypes.Structure):
     _fields_ = [("decode_chunk_tokens", ctypes.c_int32), ("force_generic", ctypes.c_int32),
-                ("prefill_query_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+                ("prefill_waves", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
 
 
 class DiffQKVError(RuntimeError):
@@ -51,12 +52,13 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not LIB_PATH.exists():
+    path = Path(os.environ.get("DIFFQKV_LIBRARY", str(LIB_PATH)))  # override: another build of the same library
+    if not path.exists():
         raise RuntimeError(
             "%s not found: the HIP library has not been built "
-            "(run `python -m paper_2501_13629_amd.build`); there is no fallback path" % LIB_PATH
+            "(run `python -m paper_2501_13629_amd.build`); there is no fallback path" % path
         )
-    lib = ctypes.CDLL(str(LIB_PATH))
+    lib = ctypes.CDLL(str(path))
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     sp = ctypes.POINTER(Shape)
     lib.diffqkv_set_tuning.restype = None
@@ -114,8 +116,8 @@ def _shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, scale) -> Shape:
     return Shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, 0.0 if scale is None else float(scale))
 
 
-def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False, prefill_query_blocks: int = 0):
-    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0, int(prefill_query_blocks))
+def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False, prefill_waves: int = 0):
+    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0, int(prefill_waves))
     load_library().diffqkv_set_tuning(ctypes.byref(t))
 
 

@@ -42,15 +42,19 @@ def stale() -> bool:
     return any(d.stat().st_mtime > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False) -> Path:
-    if not force and not stale():
+def build(force: bool = False, verbose: bool = False, extra_flags=(), out: Path | None = None) -> Path:
+    """Compile and link.  `extra_flags`/`out` build a variant of the library elsewhere (experiments)."""
+    variant = out is not None
+    if not variant and not force and not stale():
         return LIB
-    OBJ.mkdir(exist_ok=True)
+    obj_dir = OBJ if not variant else Path(str(out) + ".obj")
+    obj_dir.mkdir(exist_ok=True)
     hipcc = _hipcc()
+    target = LIB if not variant else Path(out)
 
     def compile_one(src: str) -> Path:
-        obj = OBJ / (src + ".o")
-        cmd = [hipcc, *HIPCC_FLAGS, "-I", str(INCLUDE), "-c", str(CSRC / src), "-o", str(obj)]
+        obj = obj_dir / (src + ".o")
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", str(INCLUDE), "-c", str(CSRC / src), "-o", str(obj)]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
@@ -61,13 +65,13 @@ def build(force: bool = False, verbose: bool = False) -> Path:
 
     with ThreadPoolExecutor(min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
+    tmp = target.with_suffix(".so.tmp%d" % os.getpid())
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, target)
+    return target
 
 
 if __name__ == "__main__":

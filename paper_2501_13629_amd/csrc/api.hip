@@ -115,7 +115,7 @@ void diffqkv_set_tuning(const diffqkv_tuning* t) {
     g_tuning = *t;
   else
     memset(&g_tuning, 0, sizeof g_tuning);
-  set_prefill_query_blocks(g_tuning.prefill_query_blocks);
+  set_prefill_waves(g_tuning.prefill_waves);
 }
 
 void diffqkv_set_split_event(void* hip_event) { g_split_event = (hipEvent_t)hip_event; }

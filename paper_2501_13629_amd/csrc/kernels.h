@@ -46,7 +46,7 @@ hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t s);
 bool prefill_mfma_supported(const PrefillParams& p, int dtype);
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s);
-void set_prefill_query_blocks(int qb);  // 1 or 2 32-row blocks per wavefront (experiments)
+void set_prefill_waves(int nw);  // 4 or 8 wavefronts per workgroup (experiments)
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------------------------

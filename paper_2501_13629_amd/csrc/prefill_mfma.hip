@@ -33,10 +33,9 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 constexpr int kBN = 64;  // tokens per K/V tile
 constexpr int kXcds = 8;
+constexpr float kSlack = 8.f;  // log2 units a row maximum may exceed the softmax reference
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 x = {lo, hi};
@@ -48,7 +47,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // 0, 2, 1, 3, so that the 8 tokens a lane needs for one k-step of the PV product (quads u and
 // u + 2) form one 16-byte granule.  The granule index is XOR-swizzled with the channel so that
 // both the 16-byte operand reads (32 consecutive channels) and the 8-byte transposed writes
-// (channels 8 apart) spread over the banks.
+// (channels 8 apart) spread over the banks (measured: no bank conflicts).
 __device__ __forceinline__ int vt_pos(int t) {
   const int u = (t >> 2) & 3;
   return (t & ~15) + 8 * (u & 1) + 4 * (u >> 1) + (t & 3);
@@ -62,15 +61,21 @@ struct Smem {
   uint16_t vt[2][D][kBN];
 };
 
-// QB: 32-row query blocks per wavefront (1 or 2).  With 2, every K / V^T operand read from LDS
-// feeds two matrix instructions, halving LDS traffic per flop.
-template <int D, int QB>
-__global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(PrefillParams p, int n_qtiles,
-                                                                                   int xcd_aware) {
+// Raw buffer resource over `bytes` bytes: loads take a scalar byte offset (the tile start) on top
+// of a loop-invariant per-lane offset, and rows past the end of the tensor read as zero.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// NW wavefronts of 32 query rows each per workgroup (4 or 8).  With 8 the K/V tile is staged once
+// for 256 query rows, and half of the wavefronts stage K while the other half transpose V.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams p, int n_qtiles, int xcd_aware) {
   constexpr int KS = D / 16;  // k-steps of the score product (16 channels each)
   constexpr int CB = D / 32;  // 32-channel blocks of the output
-  constexpr int kRowsPerWave = 32 * QB;
-  constexpr int kBM = kWaves * kRowsPerWave;
+  constexpr int kThreads = NW * 64;
+  constexpr int kBM = NW * 32;
   __shared__ Smem<D> sm;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -101,100 +106,96 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_mfma_kern
   const int kh = (int)(((int64_t)h * p.n_k) / p.n_q), vh = (int)(((int64_t)h * p.n_v) / p.n_q);
   const int off = p.S_k - p.S_q;        // query i sees keys j <= i + off when causal
   const int q0 = qtile * kBM;           // first query row of the workgroup
-  const int r0 = q0 + wave * kRowsPerWave;
+  const int r0 = q0 + wave * 32;        // first query row of this wavefront
 
   const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h) * p.S_q * D;
-  const uint16_t* kbase = (const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * D;
-  const uint16_t* vbase = (const uint16_t*)p.v + ((int64_t)b * p.n_v + vh) * p.S_k * D;
+  const rsrc_t k_rsrc = make_rsrc((const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * D, p.S_k * D * 2);
+  const rsrc_t v_rsrc = make_rsrc((const uint16_t*)p.v + ((int64_t)b * p.n_v + vh) * p.S_k * D, p.S_k * D * 2);
 
   // tokens this workgroup / this wavefront can see
   int wg_limit = p.S_k, wave_limit = p.S_k;
   if (p.causal) {
     const int lastq = (q0 + kBM < p.S_q ? q0 + kBM : p.S_q) - 1;
     wg_limit = lastq + off + 1;
-    int lastw = r0 + kRowsPerWave - 1;
+    int lastw = r0 + 31;
     lastw = lastw < p.S_q ? lastw : p.S_q - 1;
     wave_limit = lastw + off + 1;
   }
   const int n_tiles = (wg_limit + kBN - 1) / kBN;
 
-  // ---- Q^T as the B operand: lane (half, n) holds channels 16 ks + 8 half .. + 7 of its rows -----
-  bf16x8 qf[QB][KS];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    int row = r0 + 32 * qb + n;
+  // ---- Q^T as the B operand: lane (half, n) holds channels 16 ks + 8 half .. + 7 of its row ------
+  bf16x8 qf[KS];
+  {
+    int row = r0 + n;
     row = row < p.S_q ? row : p.S_q - 1;
     const uint16_t* qrow = qbase + (int64_t)row * D + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
   }
 
-  // ---- global -> register staging of one K/V tile --------------------------------------------------
-  // K: thread t loads the 16-byte pieces (token, chunk) = ((i*256 + t) / (D/8), (i*256 + t) % (D/8))
-  constexpr int KLD = kBN * (D / 8) / kThreads;
-  // V: 16 token quads x D/8 channel chunks, one (quad, chunk) per thread (the first 128 threads at
-  // D = 64).  Thread bits, low to high: chunk[2:0], quad-order bit 1, chunk[3] (D = 128 only),
-  // quad-order bit 0, 16-token group: lanes that write the same channel rows in one instruction
-  // then differ in the half-granule they write.
+  // ---- global -> register -> LDS staging of one K/V tile ---------------------------------------------
+  // K tile = 64 rows x D channels = one contiguous run of 16-byte pieces; K thread kt takes pieces
+  // kt, kt + 256, ...  V tile: 16 token quads x D/8 channel chunks, one (quad, chunk) per V thread:
+  // it loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to high:
+  // chunk[2:0], quad-order bit 1, chunk[3] (D = 128 only), quad-order bit 0, 16-token group --
+  // lanes that write the same channel rows in one instruction differ in the half-granule they write.
+  // With 8 wavefronts the first four are the V threads and the last four the K threads.
+  constexpr int kKThreads = 256;
+  constexpr int KLD = kBN * (D / 8) / kKThreads;
   constexpr int kChunkBits = (D == 128) ? 4 : 3;
   constexpr int kVItems = 16 * (D / 8);
-  const bool v_active = tid < kVItems;
+  const bool k_role = (NW == 4) || tid >= 256;
+  const bool v_role = tid < kVItems;
+  const int kt = tid & 255;
   const int v_c8 = (tid & 7) | ((kChunkBits == 4) ? ((tid >> 1) & 8) : 0);
   const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
   const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
-  u32x4 kst[KLD];
-  u32x4 vst[4];
+  const int v_voff = (4 * v_tq) * (D * 2) + v_c8 * 16;
+  constexpr int kStage = (NW == 4) ? 4 + KLD : 4;  // with 8 wavefronts the two roles share registers
+  u32x4 st[kStage];
+  u32x4* const kst = st + ((NW == 4) ? 4 : 0);
   auto load_tile = [&](int t0) {
+    const int tile_off = t0 * (D * 2);  // wavefront-uniform: travels in a scalar register
+    if (k_role) {
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) {
-      const int piece = i * kThreads + tid;
-      int tok = t0 + piece / (D / 8);
-      tok = tok < p.S_k ? tok : p.S_k - 1;
-      kst[i] = *(const u32x4*)(kbase + (int64_t)tok * D + (piece % (D / 8)) * 8);
+      for (int i = 0; i < KLD; ++i)
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kKThreads + kt) * 16, tile_off, 0);
     }
-    if (v_active) {
+    if (v_role) {
 #pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        int tok = t0 + 4 * v_tq + x;
-        tok = tok < p.S_k ? tok : p.S_k - 1;
-        vst[x] = *(const u32x4*)(vbase + (int64_t)tok * D + v_c8 * 8);
-      }
+      for (int x = 0; x < 4; ++x)
+        st[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (D * 2), tile_off, 0);
     }
   };
   auto store_tile = [&](int buf) {
+    if (k_role) {
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) {
-      const int piece = i * kThreads + tid;
-      *(u32x4*)&sm.k[buf][piece / (D / 8)][(piece % (D / 8)) * 8] = kst[i];
+      for (int i = 0; i < KLD; ++i) {
+        const int piece = i * kKThreads + kt;
+        *(u32x4*)&sm.k[buf][piece / (D / 8)][(piece % (D / 8)) * 8] = kst[i];
+      }
     }
-    if (v_active) {
+    if (v_role) {
       const int pos = vt_pos(4 * v_tq);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         // channel e of the chunk: word e/2, low or high half, from the 4 tokens
         const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
         u32x2 w;
-        w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
-        w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
+        w[0] = __builtin_amdgcn_perm(st[1][e >> 1], st[0][e >> 1], sel);
+        w[1] = __builtin_amdgcn_perm(st[3][e >> 1], st[2][e >> 1], sel);
         const int ch = v_c8 * 8 + e;
         *(u32x2*)&sm.vt[buf][ch][(((pos >> 3) ^ vt_swizzle(ch)) << 3) + (pos & 7)] = w;
       }
     }
   };
 
-  f32x16 acc[QB][CB];
+  f32x16 acc[CB];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+  for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[qb][cb][r] = 0.f;
-  float m_run[QB], l_run[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
-  }
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
 
   load_tile(0);
   store_tile(0);
@@ -212,80 +213,74 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_mfma_kern
     if (more) load_tile(t0 + kBN);
 
     if (!MASKED || t0 < wave_limit) {
-      // ---- S^T = K Q^T: two 32-token blocks x QB query blocks; each K operand feeds QB products --
-      f32x16 s[QB][2];
+      // ---- S^T = K Q^T for the two 32-token blocks -------------------------------------------------
+      f32x16 s[2];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
+      for (int blk = 0; blk < 2; ++blk) {
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[qb][blk][r] = 0.f;
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+        for (int r = 0; r < 16; ++r) s[blk][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
           const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sm.k[buf][32 * blk + n][16 * ks + 8 * half]);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            s[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][blk], 0, 0, 0);
-        }
-      // ---- online softmax; register r of block blk: token t0 + 32 blk + 8 (r/4) + 4 half + r%4 ---
-      uint32_t pw[QB][2][8];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;  // last visible token
-        float m_tile = -INFINITY;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float v = s[qb][blk][r];
-            if (MASKED) {
-              const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
-              v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
-              s[qb][blk][r] = v;
-            }
-            m_tile = fmaxf(m_tile, v);
-          }
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-        // scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - c m)
-        float m_new = fmaxf(m_run[qb], m_tile * p.scale_log2);
-        // a row with nothing visible yet (only in a masked tile of a later query block) keeps a
-        // finite reference so that exp2(-inf - m) stays 0 instead of NaN
-        if (MASKED) m_new = (m_new == -INFINITY) ? 0.f : m_new;
-        const float fac = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-        m_run[qb] = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i], p.scale_log2, -m_new));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i + 1], p.scale_log2, -m_new));
-            pw[qb][blk][i] = pack_bf16x2(p0, p1);
-            psum += p0 + p1;
-          }
-        l_run[qb] = l_run[qb] * fac + psum;
-        // the accumulator rescale is skipped when no row of the block raised its maximum
-        if (__builtin_amdgcn_ballot_w64(fac != 1.0f)) {
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) acc[qb][cb] *= fac;
+          s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[blk], 0, 0, 0);
         }
       }
+      // ---- online softmax; register r of block blk: token t0 + 32 blk + 8 (r/4) + 4 half + r%4 ---
+      const int row_limit = p.causal ? r0 + n + off : p.S_k - 1;  // last visible token of this row
+      float m_tile = -INFINITY;
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = s[blk][r];
+          if (MASKED) {
+            const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
+            v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
+            s[blk][r] = v;
+          }
+          m_tile = fmaxf(m_tile, v);
+        }
+      m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+      // Scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - m_ref).  The
+      // reference m_ref only has to keep the exponentials in range, it need not be the exact
+      // running maximum: it is raised (and the accumulators rescaled) only when some row's maximum
+      // exceeds it by more than kSlack, so most tiles skip the rescale.  Weights are then at most
+      // 2^kSlack, well inside bf16 / fp32 range; the final division by the row sum removes the
+      // reference.
+      const float m_cand = m_tile * p.scale_log2;
+      float m_new = m_run;
+      const bool raise = m_cand > m_run + kSlack;
+      if (__builtin_amdgcn_ballot_w64(raise)) {
+        m_new = raise ? m_cand : m_run;
+        const float fac = __builtin_amdgcn_exp2f(m_run - m_new);  // first tile: exp2(-inf) = 0
+        m_run = m_new;
+        l_run *= fac;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) acc[cb] *= fac;
+      }
+      uint32_t pw[2][8];
+      float psum = 0.f;
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i], p.scale_log2, -m_new));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i + 1], p.scale_log2, -m_new));
+          pw[blk][i] = pack_bf16x2(p0, p1);
+          psum += p0 + p1;
+        }
+      l_run += psum;
       // ---- O^T += V^T P^T: k-step kq covers tokens 16 kq .. 16 kq + 15 of the tile -----------------
 #pragma unroll
       for (int kq = 0; kq < 4; ++kq) {
         const int blk = kq >> 1, sh = (kq & 1) * 4;
+        const u32x4 pb = {pw[blk][sh], pw[blk][sh + 1], pw[blk][sh + 2], pw[blk][sh + 3]};
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
           const int ch = 32 * cb + n;
           const bf16x8 a = __builtin_bit_cast(
               bf16x8, *(const u32x4*)&sm.vt[buf][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3]);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) {
-            const u32x4 pb = {pw[qb][blk][sh], pw[qb][blk][sh + 1], pw[qb][blk][sh + 2], pw[qb][blk][sh + 3]};
-            acc[qb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb), acc[qb][cb], 0, 0, 0);
-          }
+          acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb), acc[cb], 0, 0, 0);
         }
       }
     }
@@ -299,65 +294,62 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_mfma_kern
     n_plain = vis < n_plain ? vis : n_plain;
   }
   n_plain = n_plain < n_tiles ? n_plain : n_tiles;
-  n_plain = n_plain < 0 ? 0 : n_plain;
   int it = 0;
   for (; it < n_plain; ++it) tile_step(it, std::false_type{});
   for (; it < n_tiles; ++it) tile_step(it, std::true_type{});
 
-  // ---- write this wavefront's rows: lane (half, n), acc[qb][cb][r] = row 32 qb + n, channel
+  // ---- write this wavefront's rows: lane (half, n), acc[cb][r] = row n, channel
   //      32 cb + 8 (r/4) + 4 half + r%4.  Both halves hold the full row sum after the exchange.
+  const int my_row = r0 + n;
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  if (my_row < p.S_q) {
+    const float inv = 1.f / l;
+    uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * D;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int my_row = r0 + 32 * qb + n;
-    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-    if (my_row < p.S_q) {
-      const float inv = 1.f / l;
-      uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * D;
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          u32x2 w;
-          w[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
-          w[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
-          *(u32x2*)(orow + 32 * cb + 8 * q4 + 4 * half) = w;
-        }
-      if (half == 0 && p.lse_out)
-        p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
-    }
+      for (int q4 = 0; q4 < 4; ++q4) {
+        u32x2 w;
+        w[0] = pack_bf16x2(acc[cb][4 * q4] * inv, acc[cb][4 * q4 + 1] * inv);
+        w[1] = pack_bf16x2(acc[cb][4 * q4 + 2] * inv, acc[cb][4 * q4 + 3] * inv);
+        *(u32x2*)(orow + 32 * cb + 8 * q4 + 4 * half) = w;
+      }
+    if (half == 0 && p.lse_out)
+      p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run + log2f(l)) * kLn2;
   }
 }
 
 }  // namespace
 
-// bf16, equal head widths of 64 or 128.
+// bf16, equal head widths of 64 or 128, and a K/V head no longer than the 2 GiB buffer window.
 bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
   if (dtype != 1) return false;
   if (p.d_qk != p.d_v) return false;
-  return p.d_qk == 128 || p.d_qk == 64;
+  if (p.d_qk != 128 && p.d_qk != 64) return false;
+  return (int64_t)p.S_k * p.d_qk * 2 < (1ll << 31);
 }
 
 namespace {
-int g_prefill_query_blocks = 1;  // 32-row query blocks per wavefront
-template <int D, int QB>
-hipError_t launch_qb(const PrefillParams& p, hipStream_t s) {
-  constexpr int kBM = kWaves * 32 * QB;
+int g_prefill_waves = 8;
+template <int D, int NW>
+hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
+  constexpr int kBM = NW * 32;
   const int n_qtiles = (p.S_q + kBM - 1) / kBM;
   const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
-  prefill_mfma_kernel<D, QB><<<dim3((unsigned)n_wg), dim3(kThreads), 0, s>>>(p, n_qtiles, xcd_aware);
+  prefill_mfma_kernel<D, NW><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
   return hipGetLastError();
 }
 }  // namespace
 
-void set_prefill_query_blocks(int qb) { g_prefill_query_blocks = (qb == 2) ? 2 : 1; }
+void set_prefill_waves(int nw) { g_prefill_waves = (nw == 4) ? 4 : 8; }
 
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
-  const bool two = g_prefill_query_blocks == 2;
-  if (p.d_qk == 128) return two ? launch_qb<128, 2>(p, s) : launch_qb<128, 1>(p, s);
-  return two ? launch_qb<64, 2>(p, s) : launch_qb<64, 1>(p, s);
+  const bool eight = g_prefill_waves == 8;
+  if (p.d_qk == 128) return eight ? launch_nw<128, 8>(p, s) : launch_nw<128, 4>(p, s);
+  return eight ? launch_nw<64, 8>(p, s) : launch_nw<64, 4>(p, s);
 }
 
 }  // namespace diffqkv
