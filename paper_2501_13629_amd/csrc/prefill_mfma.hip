@@ -144,8 +144,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   constexpr int KLD = kBN * (D / 8) / kKThreads;
   constexpr int kChunkBits = (D == 128) ? 4 : 3;
   constexpr int kVItems = 16 * (D / 8);
-  const bool k_role = (NW == 4) || tid >= 256;
-  const bool v_role = tid < kVItems;
+  // both roles are whole wavefronts, so the branches below are scalar
+  const bool k_role = (NW == 4) || wave >= 4;
+  const bool v_role = wave < kVItems / 64;
   const int kt = tid & 255;
   const int v_c8 = (tid & 7) | ((kChunkBits == 4) ? ((tid >> 1) & 8) : 0);
   const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
@@ -156,12 +157,13 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   u32x4* const kst = st + ((NW == 4) ? 4 : 0);
   auto load_tile = [&](int t0) {
     const int tile_off = t0 * (D * 2);  // wavefront-uniform: travels in a scalar register
+    // with 8 wavefronts the roles are exclusive (if / else), so sharing the registers is safe
     if (k_role) {
 #pragma unroll
       for (int i = 0; i < KLD; ++i)
         kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kKThreads + kt) * 16, tile_off, 0);
     }
-    if (v_role) {
+    if ((NW == 4 || !k_role) && v_role) {
 #pragma unroll
       for (int x = 0; x < 4; ++x)
         st[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (D * 2), tile_off, 0);
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
         *(u32x4*)&sm.k[buf][piece / (D / 8)][(piece % (D / 8)) * 8] = kst[i];
       }
     }
-    if (v_role) {
+    if ((NW == 4 || !k_role) && v_role) {
       const int pos = vt_pos(4 * v_tq);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -199,6 +201,11 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
 
   load_tile(0);
   store_tile(0);
+  // Pin the arrival of Q before the loop: otherwise the compiler, not knowing whether these loads
+  // are still in flight when the loop is entered, makes every iteration wait on the vector-memory
+  // counter -- and with it on the next tile's staging loads -- before each matrix instruction.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]));
   __syncthreads();
 
   // One tile step.  MASKED is a compile-time flag: tiles strictly below the diagonal of this
@@ -214,17 +221,19 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
 
     if (!MASKED || t0 < wave_limit) {
       // ---- S^T = K Q^T for the two 32-token blocks -------------------------------------------------
+      // (the two blocks alternate so that consecutive matrix instructions are independent)
       f32x16 s[2];
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk) {
+      for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[blk][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
           const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sm.k[buf][32 * blk + n][16 * ks + 8 * half]);
           s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[blk], 0, 0, 0);
         }
-      }
       // ---- online softmax; register r of block blk: token t0 + 32 blk + 8 (r/4) + 4 half + r%4 ---
       const int row_limit = p.causal ? r0 + n + off : p.S_k - 1;  // last visible token of this row
       float m_tile = -INFINITY;
