@@ -220,25 +220,26 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
     if (more) load_tile(t0 + kBN);
 
     if (!MASKED || t0 < wave_limit) {
-      // ---- S^T = K Q^T for the two 32-token blocks -------------------------------------------------
-      // (the two blocks alternate so that consecutive matrix instructions are independent)
-      f32x16 s[2];
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[blk][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-          const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sm.k[buf][32 * blk + n][16 * ks + 8 * half]);
-          s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[blk], 0, 0, 0);
-        }
-      // ---- online softmax; register r of block blk: token t0 + 32 blk + 8 (r/4) + 4 half + r%4 ---
+      // Each 32-token block is one online-softmax step of its own:
+      //     S^T(blk) = K Q^T  ->  softmax(blk)  ->  O^T += V^T P^T(blk)
+      // and the two blocks are written interleaved -- the score product of block 1 between the
+      // softmax pieces of block 0, the softmax of block 1 between the output products of block 0 --
+      // so that the vector ALU (exponentials) and the matrix cores work at the same time.
       const int row_limit = p.causal ? r0 + n + off : p.S_k - 1;  // last visible token of this row
-      float m_tile = -INFINITY;
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+      f32x16 s[2];
+      uint32_t pw[2][8];
+      auto score_step = [&](int blk, int ks) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sm.k[buf][32 * blk + n][16 * ks + 8 * half]);
+        s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[blk], 0, 0, 0);
+      };
+      // softmax reference for one block; register r: token t0 + 32 blk + 8 (r/4) + 4 half + r%4.
+      // Scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - m_ref).  The
+      // reference m_ref only has to keep the exponentials in range, it need not be the exact
+      // running maximum: it is raised (and the accumulators rescaled) only when some row's maximum
+      // exceeds it by more than kSlack, so most blocks skip the rescale.  Weights are then at most
+      // 2^kSlack, well inside bf16 / fp32 range; the final division by the row sum removes it.
+      auto reference = [&](int blk) {
+        float m_blk = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float v = s[blk][r];
@@ -247,51 +248,65 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
             v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
             s[blk][r] = v;
           }
-          m_tile = fmaxf(m_tile, v);
+          m_blk = fmaxf(m_blk, v);
         }
-      m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-      // Scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - m_ref).  The
-      // reference m_ref only has to keep the exponentials in range, it need not be the exact
-      // running maximum: it is raised (and the accumulators rescaled) only when some row's maximum
-      // exceeds it by more than kSlack, so most tiles skip the rescale.  Weights are then at most
-      // 2^kSlack, well inside bf16 / fp32 range; the final division by the row sum removes the
-      // reference.
-      const float m_cand = m_tile * p.scale_log2;
-      float m_new = m_run;
-      const bool raise = m_cand > m_run + kSlack;
-      if (__builtin_amdgcn_ballot_w64(raise)) {
-        m_new = raise ? m_cand : m_run;
-        const float fac = __builtin_amdgcn_exp2f(m_run - m_new);  // first tile: exp2(-inf) = 0
-        m_run = m_new;
-        l_run *= fac;
+        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
+        const float m_cand = m_blk * p.scale_log2;
+        const bool raise = m_cand > m_run + kSlack;
+        float fac = 1.f;
+        if (__builtin_amdgcn_ballot_w64(raise)) {
+          const float m_new = raise ? m_cand : m_run;
+          fac = __builtin_amdgcn_exp2f(m_run - m_new);  // first block: exp2(-inf) = 0
+          m_run = m_new;
+          l_run *= fac;
+        }
+        return fac;  // the caller rescales the accumulators once they hold everything older
+      };
+      auto rescale = [&](float fac) {
+        if (__builtin_amdgcn_ballot_w64(fac != 1.f)) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) acc[cb] *= fac;
-      }
-      uint32_t pw[2][8];
-      float psum = 0.f;
+          for (int cb = 0; cb < CB; ++cb) acc[cb] *= fac;
+        }
+      };
+      auto weights_step = [&](int blk, int i) {  // two of the block's 16 weights
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i], p.scale_log2, -m_run));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i + 1], p.scale_log2, -m_run));
+        pw[blk][i] = pack_bf16x2(p0, p1);
+        l_run += p0 + p1;
+      };
+      auto output_step = [&](int blk, int kh2, int cb) {  // k-step kh2 (16 tokens) of block blk
+        const int kq = 2 * blk + kh2, sh = kh2 * 4;
+        const u32x4 pb = {pw[blk][sh], pw[blk][sh + 1], pw[blk][sh + 2], pw[blk][sh + 3]};
+        const int ch = 32 * cb + n;
+        const bf16x8 a = __builtin_bit_cast(
+            bf16x8, *(const u32x4*)&sm.vt[buf][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3]);
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb), acc[cb], 0, 0, 0);
+      };
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i], p.scale_log2, -m_new));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i + 1], p.scale_log2, -m_new));
-          pw[blk][i] = pack_bf16x2(p0, p1);
-          psum += p0 + p1;
-        }
-      l_run += psum;
-      // ---- O^T += V^T P^T: k-step kq covers tokens 16 kq .. 16 kq + 15 of the tile -----------------
+        for (int r = 0; r < 16; ++r) s[blk][r] = 0.f;
 #pragma unroll
-      for (int kq = 0; kq < 4; ++kq) {
-        const int blk = kq >> 1, sh = (kq & 1) * 4;
-        const u32x4 pb = {pw[blk][sh], pw[blk][sh + 1], pw[blk][sh + 2], pw[blk][sh + 3]};
+      for (int ks = 0; ks < KS; ++ks) score_step(0, ks);
+      rescale(reference(0));
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-          const int ch = 32 * cb + n;
-          const bf16x8 a = __builtin_bit_cast(
-              bf16x8, *(const u32x4*)&sm.vt[buf][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3]);
-          acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb), acc[cb], 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks) {
+        score_step(1, ks);
+        if (ks * 8 / KS != (ks + 1) * 8 / KS || KS == 8) {
+#pragma unroll
+          for (int i = ks * 8 / KS; i < (ks + 1) * 8 / KS; ++i) weights_step(0, i);
         }
       }
+      const float fac1 = reference(1);
+#pragma unroll
+      for (int j = 0; j < 2 * CB; ++j) {
+        output_step(0, j / CB, j % CB);
+#pragma unroll
+        for (int i = j * 8 / (2 * CB); i < (j + 1) * 8 / (2 * CB); ++i) weights_step(1, i);
+      }
+      rescale(fac1);  // block 0's weights were taken against the older reference: apply it after them
+#pragma unroll
+      for (int j = 0; j < 2 * CB; ++j) output_step(1, j / CB, j % CB);
     }
     if (more) store_tile(buf ^ 1);
     __syncthreads();
