@@ -139,6 +139,35 @@ int diffqkv_prefill(const diffqkv_shape* shape /* host */, const void* q, const 
                     float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * KV-cache append (section 3.2, "KV Cache": the store side of the cache; K and V are separate
+ * tensors with their own head counts -- "differential management of KV cache").  For every sequence
+ * b, copies k_new[b] into token row positions[b] of the K cache and v_new[b] into the same row of
+ * the V cache.  Call it before the attention of the same step: the paper concatenates the current
+ * token first.  Bit exact.
+ *
+ *   k_new  [B, n_k, d_qk]   v_new [B, n_v, d_v]   dense, dtype of the cache
+ *   k_cache / v_cache and their strides: as in diffqkv_decode (k_pool / v_pool and page strides as
+ *            in diffqkv_decode_paged)
+ *   positions    int32 [B] on the device: the row to write (the sequence length before the append)
+ *   T_cap        rows per sequence in the contiguous cache; the paged capacity is
+ *                max_pages * page_size.  A position outside [0, capacity) writes nothing.
+ *   seqlens_out  int32 [B] on the device or NULL: receives positions[b] + 1 for every written row
+ *                (it may alias `positions`)
+ * Head widths must make every head row a multiple of 16 bytes.  shape->n_q and softmax_scale are
+ * not used by these calls (n_q must still be a valid multiple of n_k and n_v).
+ */
+int diffqkv_append(const diffqkv_shape* shape /* host */, const void* k_new, const void* v_new,
+                   void* k_cache, void* v_cache, int64_t k_stride_b, int64_t k_stride_h,
+                   int64_t k_stride_t, int64_t v_stride_b, int64_t v_stride_h, int64_t v_stride_t,
+                   const int32_t* positions, int32_t T_cap, int32_t* seqlens_out, void* hip_stream);
+int diffqkv_append_paged(const diffqkv_shape* shape /* host */, const void* k_new, const void* v_new,
+                         void* k_pool, void* v_pool, int64_t k_stride_page, int64_t k_stride_h,
+                         int64_t k_stride_t, int64_t v_stride_page, int64_t v_stride_h,
+                         int64_t v_stride_t, const int32_t* block_table, int32_t max_pages,
+                         int32_t page_size, const int32_t* positions, int32_t* seqlens_out,
+                         void* hip_stream);
+
+/*
  * Measurement aid: reads `bytes` (a multiple of 16) from `src` with 128-bit loads, as fast as the
  * memory system allows, and writes one float per workgroup to `sink` (at least 4096 floats) so the
  * reads cannot be elided.  Used to measure the achievable HBM read rate beside the decode kernels.

@@ -193,3 +193,44 @@ def lse_merge(o_parts, lse_parts):
     lse = np.empty((1,), dtype=np.float64)
     _load().oracle_lse_merge(S, d_v, _ptr(o_parts), _ptr(lse_parts), _ptr(out), _ptr(lse))
     return out, float(lse[0])
+
+
+def append(k_new, v_new, k_cache, v_cache, positions):
+    """KV-cache store (section 3.2, "KV Cache"): returns copies of the caches with k_new[b], v_new[b]
+    written at token row positions[b]; rows outside [0, T_cap) are skipped.  Plain element copies:
+    k_cache [B,n_k,T_cap,d_qk], v_cache [B,n_v,T_cap,d_v], k_new [B,n_k,d_qk], v_new [B,n_v,d_v]."""
+    k_out, v_out = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    B, n_k, T_cap, d_qk = k_out.shape
+    n_v, d_v = v_out.shape[1], v_out.shape[3]
+    for b in range(B):
+        t = int(positions[b])
+        if t < 0 or t >= T_cap:
+            continue
+        for h in range(n_k):
+            for c in range(d_qk):
+                k_out[b, h, t, c] = k_new[b, h, c]
+        for h in range(n_v):
+            for c in range(d_v):
+                v_out[b, h, t, c] = v_new[b, h, c]
+    return k_out, v_out
+
+
+def append_paged(k_new, v_new, k_pool, v_pool, block_table, positions):
+    """Paged KV-cache store: token row positions[b] of sequence b is slot positions[b] % P of page
+    block_table[b, positions[b] // P].  Returns copies of the pools."""
+    k_out, v_out = np.array(k_pool, copy=True), np.array(v_pool, copy=True)
+    n_pages, n_k, P, d_qk = k_out.shape
+    n_v, d_v = v_out.shape[1], v_out.shape[3]
+    B, max_pages = block_table.shape
+    for b in range(B):
+        t = int(positions[b])
+        if t < 0 or t >= max_pages * P:
+            continue
+        page, slot = int(block_table[b, t // P]), t % P
+        for h in range(n_k):
+            for c in range(d_qk):
+                k_out[page, h, slot, c] = k_new[b, h, c]
+        for h in range(n_v):
+            for c in range(d_v):
+                v_out[page, h, slot, c] = v_new[b, h, c]
+    return k_out, v_out

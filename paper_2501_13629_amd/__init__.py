@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     BF16,
     F32,
     DiffQKVError,
+    diffqkv_append,
+    diffqkv_append_paged,
     diffqkv_decode,
     diffqkv_decode_paged,
     diffqkv_decode_workspace_bytes,

@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 EXPORTS = (
     "diffqkv_set_tuning", "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_paged",
     "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_probe_stream_read", "diffqkv_strerror",
-    "diffqkv_version", "diffqkv_set_split_event",
+    "diffqkv_version", "diffqkv_set_split_event", "diffqkv_append", "diffqkv_append_paged",
 )
 
 
@@ -73,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.diffqkv_prefill_workspace_bytes.argtypes = [sp, i32, i32]
     lib.diffqkv_prefill.restype = ctypes.c_int
     lib.diffqkv_prefill.argtypes = [sp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.diffqkv_append.restype = ctypes.c_int
+    lib.diffqkv_append.argtypes = [sp, vp, vp, vp, vp] + [i64] * 6 + [vp, i32, vp, vp]
+    lib.diffqkv_append_paged.restype = ctypes.c_int
+    lib.diffqkv_append_paged.argtypes = [sp, vp, vp, vp, vp] + [i64] * 6 + [vp, i32, i32, vp, vp, vp]
     lib.diffqkv_probe_stream_read.restype = ctypes.c_int
     lib.diffqkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.diffqkv_strerror.restype = ctypes.c_char_p
@@ -232,6 +236,54 @@ def diffqkv_prefill(q, k, v, causal=True, scale=None, out=None, lse_out=None, wa
         ctypes.byref(s), _ptr(q), _ptr(k), _ptr(v), int(S_q), int(S_k), 1 if causal else 0, _ptr(out),
         _ptr(lse_out), None, 0, _stream(q)))
     return (out, lse_out) if (want_lse or lse_out is not None) else out
+
+
+def diffqkv_append(k_new, v_new, k_cache, v_cache, positions, seqlens_out=None):
+    """k_new [B,n_k,d_qk], v_new [B,n_v,d_v] written into row positions[b] of k_cache [B,n_k,T_cap,d_qk]
+    and v_cache [B,n_v,T_cap,d_v] (in place).  positions: int32 device [B]."""
+    _dev(k_new, v_new, k_cache, v_cache, positions, seqlens_out)
+    dt = _dtype_code(k_cache)
+    if _dtype_code(k_new) != dt or _dtype_code(v_new) != dt or _dtype_code(v_cache) != dt:
+        raise TypeError("k_new, v_new and the caches must share a dtype")
+    if not (k_new.is_contiguous() and v_new.is_contiguous() and positions.is_contiguous()):
+        raise ValueError("k_new, v_new and positions must be contiguous")
+    if positions.dtype != torch.int32 or (seqlens_out is not None and seqlens_out.dtype != torch.int32):
+        raise TypeError("positions and seqlens_out must be int32")
+    B, n_k, T_cap, d_qk = k_cache.shape
+    _, n_v, _, d_v = v_cache.shape
+    if tuple(k_new.shape) != (B, n_k, d_qk) or tuple(v_new.shape) != (B, n_v, d_v):
+        raise ValueError("k_new / v_new do not match the caches")
+    if k_cache.stride(3) != 1 or v_cache.stride(3) != 1:
+        raise ValueError("the channel dimension of the caches must be contiguous")
+    n_q = n_k * n_v  # any common multiple: the append does not involve query heads
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, None)
+    ks, vs = k_cache.stride(), v_cache.stride()
+    _check(load_library().diffqkv_append(
+        ctypes.byref(s), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), ks[0], ks[1], ks[2], vs[0], vs[1],
+        vs[2], _ptr(positions), int(T_cap), _ptr(seqlens_out), _stream(k_cache)))
+
+
+def diffqkv_append_paged(k_new, v_new, k_pool, v_pool, block_table, positions, seqlens_out=None):
+    """Paged variant: k_pool [n_pages,n_k,P,d_qk], v_pool [n_pages,n_v,P,d_v], block_table int32 [B,max_pages]."""
+    _dev(k_new, v_new, k_pool, v_pool, block_table, positions, seqlens_out)
+    dt = _dtype_code(k_pool)
+    if _dtype_code(k_new) != dt or _dtype_code(v_new) != dt or _dtype_code(v_pool) != dt:
+        raise TypeError("k_new, v_new and the pools must share a dtype")
+    if not (k_new.is_contiguous() and v_new.is_contiguous() and positions.is_contiguous()
+            and block_table.is_contiguous()):
+        raise ValueError("k_new, v_new, positions and block_table must be contiguous")
+    if positions.dtype != torch.int32 or block_table.dtype != torch.int32:
+        raise TypeError("positions and block_table must be int32")
+    _, n_k, P, d_qk = k_pool.shape
+    _, n_v, _, d_v = v_pool.shape
+    B, max_pages = block_table.shape
+    if tuple(k_new.shape) != (B, n_k, d_qk) or tuple(v_new.shape) != (B, n_v, d_v):
+        raise ValueError("k_new / v_new do not match the pools")
+    s = _shape(B, n_k * n_v, n_k, n_v, d_qk, d_v, dt, None)
+    ks, vs = k_pool.stride(), v_pool.stride()
+    _check(load_library().diffqkv_append_paged(
+        ctypes.byref(s), _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), ks[0], ks[1], ks[2], vs[0], vs[1],
+        vs[2], _ptr(block_table), int(max_pages), int(P), _ptr(positions), _ptr(seqlens_out), _stream(k_pool)))
 
 
 def diffqkv_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor):

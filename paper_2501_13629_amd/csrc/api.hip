@@ -205,6 +205,73 @@ int diffqkv_decode_paged(const diffqkv_shape* shape, const void* q, const void* 
   return run_decode(shape, p, true, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
+static int run_append(const diffqkv_shape* shape, const void* k_new, const void* v_new, void* k, void* v,
+                      int64_t k_s0, int64_t k_sh, int64_t k_st, int64_t v_s0, int64_t v_sh, int64_t v_st,
+                      const int32_t* block_table, int32_t max_pages, int32_t page_size,
+                      const int32_t* positions, int32_t capacity, int32_t* seqlens_out, bool paged,
+                      void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (capacity < 0) return DIFFQKV_ERR_SHAPE;
+  const int64_t es = (int64_t)elem_size(shape->dtype);
+  if ((shape->d_qk * es) % 16 || (shape->d_v * es) % 16) return DIFFQKV_ERR_SHAPE;
+  if (shape->B > 0) {
+    if (!k_new || !v_new || !positions) return DIFFQKV_ERR_NULL;
+    if (capacity > 0 && (!k || !v)) return DIFFQKV_ERR_NULL;
+    if (paged && capacity > 0 && !block_table) return DIFFQKV_ERR_NULL;
+  }
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k) || !aligned16(v)) return DIFFQKV_ERR_ALIGN;
+  const int dt = shape->dtype;
+  if (!stride_ok(k_s0, dt) || !stride_ok(k_sh, dt) || !stride_ok(k_st, dt) || !stride_ok(v_s0, dt) ||
+      !stride_ok(v_sh, dt) || !stride_ok(v_st, dt))
+    return DIFFQKV_ERR_ALIGN;
+  if (k_st < shape->d_qk || v_st < shape->d_v) return DIFFQKV_ERR_SHAPE;
+  AppendParams p = {};
+  p.k_new = k_new;
+  p.v_new = v_new;
+  p.k = k;
+  p.v = v;
+  p.k_sb = k_s0 * es;
+  p.k_sh = k_sh * es;
+  p.k_st = k_st * es;
+  p.v_sb = v_s0 * es;
+  p.v_sh = v_sh * es;
+  p.v_st = v_st * es;
+  p.positions = positions;
+  p.seqlens_out = seqlens_out;
+  p.block_table = block_table;
+  p.max_pages = max_pages;
+  p.page_size = page_size;
+  p.capacity = capacity;
+  p.B = shape->B;
+  p.n_k = shape->n_k;
+  p.n_v = shape->n_v;
+  p.row_k_bytes = (int32_t)(shape->d_qk * es);
+  p.row_v_bytes = (int32_t)(shape->d_v * es);
+  if (shape->B == 0 || capacity == 0) return DIFFQKV_OK;
+  return launch_append(p, paged, (hipStream_t)hip_stream) == hipSuccess ? DIFFQKV_OK : DIFFQKV_ERR_HIP;
+}
+
+int diffqkv_append(const diffqkv_shape* shape, const void* k_new, const void* v_new, void* k_cache,
+                   void* v_cache, int64_t k_stride_b, int64_t k_stride_h, int64_t k_stride_t,
+                   int64_t v_stride_b, int64_t v_stride_h, int64_t v_stride_t,
+                   const int32_t* positions, int32_t T_cap, int32_t* seqlens_out, void* hip_stream) {
+  return run_append(shape, k_new, v_new, k_cache, v_cache, k_stride_b, k_stride_h, k_stride_t, v_stride_b,
+                    v_stride_h, v_stride_t, nullptr, 0, 0, positions, T_cap, seqlens_out, false, hip_stream);
+}
+
+int diffqkv_append_paged(const diffqkv_shape* shape, const void* k_new, const void* v_new, void* k_pool,
+                         void* v_pool, int64_t k_stride_page, int64_t k_stride_h, int64_t k_stride_t,
+                         int64_t v_stride_page, int64_t v_stride_h, int64_t v_stride_t,
+                         const int32_t* block_table, int32_t max_pages, int32_t page_size,
+                         const int32_t* positions, int32_t* seqlens_out, void* hip_stream) {
+  if (max_pages < 0 || page_size <= 0) return DIFFQKV_ERR_SHAPE;
+  if ((int64_t)max_pages * page_size > INT32_MAX) return DIFFQKV_ERR_SHAPE;
+  return run_append(shape, k_new, v_new, k_pool, v_pool, k_stride_page, k_stride_h, k_stride_t, v_stride_page,
+                    v_stride_h, v_stride_t, block_table, max_pages, page_size, positions,
+                    max_pages * page_size, seqlens_out, true, hip_stream);
+}
+
 size_t diffqkv_prefill_workspace_bytes(const diffqkv_shape* shape, int32_t S_q, int32_t S_k) {
   (void)shape;
   (void)S_q;

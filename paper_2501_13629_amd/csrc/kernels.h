@@ -38,6 +38,23 @@ struct PrefillParams {
   float scale_log2;
 };
 
+// Strides here are in BYTES (the boundary converts).
+struct AppendParams {
+  const void* k_new;  // [B, n_k, d_qk]
+  const void* v_new;  // [B, n_v, d_v]
+  void* k;            // contiguous cache or page pool
+  void* v;
+  int64_t k_sb, k_sh, k_st;  // batch (or page) / head / token strides
+  int64_t v_sb, v_sh, v_st;
+  const int32_t* positions;    // device [B]: token index to write
+  int32_t* seqlens_out;        // device [B] or nullptr: receives position + 1
+  const int32_t* block_table;  // device [B, max_pages], paged only
+  int32_t max_pages, page_size;
+  int32_t capacity;            // positions >= capacity are skipped
+  int32_t B, n_k, n_v;
+  int32_t row_k_bytes, row_v_bytes;  // d_qk, d_v in bytes (multiples of 16)
+};
+
 // dtype: 0 = fp32, 1 = bf16 (diffqkv_dtype).  All return a hipError_t from the launch.
 hipError_t launch_decode_generic(const DecodeParams& p, int dtype, bool paged, hipStream_t s);
 bool decode_mfma_supported(const DecodeParams& p, int dtype);
@@ -47,6 +64,7 @@ hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t
 bool prefill_mfma_supported(const PrefillParams& p, int dtype);
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s);
 void set_prefill_waves(int nw);  // 4 or 8 wavefronts per workgroup (experiments)
+hipError_t launch_append(const AppendParams& p, bool paged, hipStream_t s);
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------------------------

@@ -31,7 +31,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) >= 9
+    assert len(names) >= 12
     for name in names:
         assert hasattr(lib, name), name
     assert set(names) == set(binding.EXPORTS)
@@ -131,3 +131,20 @@ def test_binding_refuses_cpu_tensors():
     v = torch.zeros(1, 2, 8, 64)
     with pytest.raises(RuntimeError, match="GPU only"):
         binding.diffqkv_decode(q, k, v)
+
+
+def test_append_validation_codes(lib):
+    vp = ctypes.c_void_p
+    s = shape()
+
+    def app(k_new=0x1000, pos=0x6000, kst=(8192, 4096, 64), cap=64, sh=s):
+        return lib.diffqkv_append(ctypes.byref(sh), vp(k_new), vp(0x2000), vp(0x3000), vp(0x4000), *kst, 8192, 4096,
+                                  64, vp(pos), cap, None, None)
+
+    assert app(k_new=0) == E_NULL
+    assert app(pos=0) == E_NULL
+    assert app(cap=-1) == E_SHAPE
+    assert app(kst=(8192, 4096, 60)) == E_ALIGN
+    assert app(sh=shape(B=0)) == OK
+    assert lib.diffqkv_append_paged(ctypes.byref(s), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), 4096, 1024, 64,
+                                    4096, 1024, 64, vp(0x7000), 4, 0, vp(0x6000), None, None) == E_SHAPE

@@ -251,3 +251,51 @@ def test_cost_model_golden():
         assert inputs.kv_bytes_per_token(cfg) == 2 * elems
         per_tok[name] = inputs.kv_bytes_per_token(cfg)
     assert (per_tok["gqa_std"] - per_tok["sigma_1p5b"]) / per_tok["gqa_std"] == rows["limit_reduction"][0]
+
+
+# KV-cache store: appending token t and attending over t+1 rows is attention over the concatenation
+# (the paper concatenates k_t, v_t to the cache before attending); everything else stays untouched.
+def test_append_then_decode_is_decode_on_concatenation():
+    B, n_q, n_k, n_v, d, T_cap = 3, 8, 2, 4, 8, 12
+    q, k, v = rnd((B, n_q, d), 40), rnd((B, n_k, T_cap, d), 41), rnd((B, n_v, T_cap, d), 42)
+    k_new, v_new = rnd((B, n_k, d), 43), rnd((B, n_v, d), 44)
+    pos = np.array([0, 5, 11], np.int32)
+    k2, v2 = oracle.append(k_new, v_new, k, v, pos)
+    for b in range(B):
+        t = int(pos[b])
+        kc = np.concatenate([k[b : b + 1, :, :t], k_new[b : b + 1, :, None]], axis=2)
+        vc = np.concatenate([v[b : b + 1, :, :t], v_new[b : b + 1, :, None]], axis=2)
+        ref, _ = brute.diffqkv_decode_by_expansion(q[b : b + 1], kc, vc, oracle.default_scale(d))
+        got, _ = oracle.decode(q[b : b + 1], k2[b : b + 1], v2[b : b + 1], T=t + 1)
+        rel_close(got, ref)
+        mask = np.ones(T_cap, bool)
+        mask[t] = False
+        assert np.array_equal(k2[b][:, mask], k[b][:, mask]) and np.array_equal(v2[b][:, mask], v[b][:, mask])
+    # out-of-range positions write nothing
+    k3, v3 = oracle.append(k_new, v_new, k, v, np.array([-1, T_cap, 99], np.int32))
+    assert np.array_equal(k3, k) and np.array_equal(v3, v)
+
+
+def test_append_paged_matches_contiguous_view():
+    cfg = inputs.config("paged_ragged", B=3, n_q=8, n_k=2, n_v=4, d_qk=16, d_v=16, page_size=4, seqlens=[3, 8, 10],
+                        max_pages=4)
+    d = inputs.make_paged(cfg)
+    kp, vp = inputs.as_numpy(d["k_pool"]), inputs.as_numpy(d["v_pool"])
+    bt = d["block_table"].numpy().copy()
+    # sequence 1 is exactly at a page boundary: give it (and every sequence) a spare page
+    used = set(bt[bt >= 0].tolist())
+    spare = [p for p in range(kp.shape[0] + 3) if p not in used]
+    kp = np.concatenate([kp, np.zeros((3,) + kp.shape[1:], kp.dtype)])
+    vp = np.concatenate([vp, np.zeros((3,) + vp.shape[1:], vp.dtype)])
+    for b in range(3):
+        row = bt[b]
+        row[np.argmax(row < 0)] = spare[b]
+    pos = d["seqlens"].numpy()
+    k_new, v_new = to_bf16_bits(rnd((3, 2, 16), 45)), to_bf16_bits(rnd((3, 4, 16), 46))
+    kp2, vp2 = oracle.append_paged(k_new, v_new, kp, vp, bt, pos)
+    kc, vc = brute.gather_paged(kp2, bt, pos + 1, 16), brute.gather_paged(vp2, bt, pos + 1, 16)
+    for b in range(3):
+        assert np.array_equal(kc[b, :, pos[b]], k_new[b]) and np.array_equal(vc[b, :, pos[b]], v_new[b])
+    kc0, vc0 = brute.gather_paged(kp, bt, pos, 16), brute.gather_paged(vp, bt, pos, 16)
+    for b in range(3):
+        assert np.array_equal(kc[b, :, : pos[b]], kc0[b, :, : pos[b]])
