@@ -19,7 +19,7 @@ hipEvent_t g_split_event = nullptr;
 constexpr int kComputeUnits = 256;
 constexpr int kTargetWorkgroups = kComputeUnits;
 constexpr int kChunkQuantum = 128;  // one workgroup step of the decode kernels
-constexpr int kMinChunk = 256;
+constexpr int kMinChunk = 128;
 constexpr int kMaxChunk = 8192;
 // With per-sequence lengths the work per (sequence, head) is uneven and unknown on the host:
 // shorter chunks let the hardware dispatcher balance it.
