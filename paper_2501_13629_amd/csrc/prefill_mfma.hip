@@ -54,11 +54,11 @@ __device__ __forceinline__ int vt_pos(int t) {
 }
 __device__ __forceinline__ int vt_swizzle(int ch) { return (ch ^ (ch >> 3)) & 7; }
 
-template <int D>
+template <int DQK, int DV>
 struct Smem {
-  static constexpr int kKPitch = D + 8;  // bf16 elements per K row (16 B of padding)
+  static constexpr int kKPitch = DQK + 8;  // bf16 elements per K row (16 B of padding)
   uint16_t k[2][kBN][kKPitch];
-  uint16_t vt[2][D][kBN];
+  uint16_t vt[2][DV][kBN];
 };
 
 // Raw buffer resource over `bytes` bytes: loads take a scalar byte offset (the tile start) on top
@@ -70,13 +70,13 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes) {
 
 // NW wavefronts of 32 query rows each per workgroup (4 or 8).  With 8 the K/V tile is staged once
 // for 256 query rows, and half of the wavefronts stage K while the other half transpose V.
-template <int D, int NW>
+template <int DQK, int DV, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams p, int n_qtiles, int xcd_aware) {
-  constexpr int KS = D / 16;  // k-steps of the score product (16 channels each)
-  constexpr int CB = D / 32;  // 32-channel blocks of the output
+  constexpr int KS = DQK / 16;  // k-steps of the score product (16 channels each)
+  constexpr int CB = DV / 32;   // 32-channel blocks of the output
   constexpr int kThreads = NW * 64;
   constexpr int kBM = NW * 32;
-  __shared__ Smem<D> sm;
+  __shared__ Smem<DQK, DV> sm;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -108,9 +108,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   const int q0 = qtile * kBM;           // first query row of the workgroup
   const int r0 = q0 + wave * 32;        // first query row of this wavefront
 
-  const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h) * p.S_q * D;
-  const rsrc_t k_rsrc = make_rsrc((const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * D, p.S_k * D * 2);
-  const rsrc_t v_rsrc = make_rsrc((const uint16_t*)p.v + ((int64_t)b * p.n_v + vh) * p.S_k * D, p.S_k * D * 2);
+  const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h) * p.S_q * DQK;
+  const rsrc_t k_rsrc = make_rsrc((const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * DQK, p.S_k * DQK * 2);
+  const rsrc_t v_rsrc = make_rsrc((const uint16_t*)p.v + ((int64_t)b * p.n_v + vh) * p.S_k * DV, p.S_k * DV * 2);
 
   // tokens this workgroup / this wavefront can see
   int wg_limit = p.S_k, wave_limit = p.S_k;
@@ -128,22 +128,22 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   {
     int row = r0 + n;
     row = row < p.S_q ? row : p.S_q - 1;
-    const uint16_t* qrow = qbase + (int64_t)row * D + half * 8;
+    const uint16_t* qrow = qbase + (int64_t)row * DQK + half * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
   }
 
   // ---- global -> register -> LDS staging of one K/V tile ---------------------------------------------
-  // K tile = 64 rows x D channels = one contiguous run of 16-byte pieces; K thread kt takes pieces
-  // kt, kt + 256, ...  V tile: 16 token quads x D/8 channel chunks, one (quad, chunk) per V thread:
-  // it loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to high:
-  // chunk[2:0], quad-order bit 1, chunk[3] (D = 128 only), quad-order bit 0, 16-token group --
+  // K tile = 64 rows x d_qk channels = one contiguous run of 16-byte pieces; K thread kt takes
+  // pieces kt, kt + 256, ...  V tile: 16 token quads x d_v/8 channel chunks, one (quad, chunk) per V
+  // thread: it loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to
+  // high: chunk[2:0], quad-order bit 1, chunk[3] (d_v = 128 only), quad-order bit 0, 16-token group --
   // lanes that write the same channel rows in one instruction differ in the half-granule they write.
   // With 8 wavefronts the first four are the V threads and the last four the K threads.
   constexpr int kKThreads = 256;
-  constexpr int KLD = kBN * (D / 8) / kKThreads;
-  constexpr int kChunkBits = (D == 128) ? 4 : 3;
-  constexpr int kVItems = 16 * (D / 8);
+  constexpr int KLD = kBN * (DQK / 8) / kKThreads;
+  constexpr int kChunkBits = (DV == 128) ? 4 : 3;
+  constexpr int kVItems = 16 * (DV / 8);
   // both roles are whole wavefronts, so the branches below are scalar
   const bool k_role = (NW == 4) || wave >= 4;
   const bool v_role = wave < kVItems / 64;
@@ -151,22 +151,22 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   const int v_c8 = (tid & 7) | ((kChunkBits == 4) ? ((tid >> 1) & 8) : 0);
   const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
   const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
-  const int v_voff = (4 * v_tq) * (D * 2) + v_c8 * 16;
+  const int v_voff = (4 * v_tq) * (DV * 2) + v_c8 * 16;
   constexpr int kStage = (NW == 4) ? 4 + KLD : 4;  // with 8 wavefronts the two roles share registers
   u32x4 st[kStage];
   u32x4* const kst = st + ((NW == 4) ? 4 : 0);
   auto load_tile = [&](int t0) {
-    const int tile_off = t0 * (D * 2);  // wavefront-uniform: travels in a scalar register
+    // tile starts, wavefront-uniform: they travel in scalar registers
     // with 8 wavefronts the roles are exclusive (if / else), so sharing the registers is safe
     if (k_role) {
 #pragma unroll
       for (int i = 0; i < KLD; ++i)
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kKThreads + kt) * 16, tile_off, 0);
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kKThreads + kt) * 16, t0 * (DQK * 2), 0);
     }
     if ((NW == 4 || !k_role) && v_role) {
 #pragma unroll
       for (int x = 0; x < 4; ++x)
-        st[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (D * 2), tile_off, 0);
+        st[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2), t0 * (DV * 2), 0);
     }
   };
   auto store_tile = [&](int buf) {
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
 #pragma unroll
       for (int i = 0; i < KLD; ++i) {
         const int piece = i * kKThreads + kt;
-        *(u32x4*)&sm.k[buf][piece / (D / 8)][(piece % (D / 8)) * 8] = kst[i];
+        *(u32x4*)&sm.k[buf][piece / (DQK / 8)][(piece % (DQK / 8)) * 8] = kst[i];
       }
     }
     if ((NW == 4 || !k_role) && v_role) {
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   const float l = l_run + __shfl_xor(l_run, 32, 64);
   if (my_row < p.S_q) {
     const float inv = 1.f / l;
-    uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * D;
+    uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * DV;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -345,24 +345,24 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
 
 }  // namespace
 
-// bf16, equal head widths of 64 or 128, and a K/V head no longer than the 2 GiB buffer window.
+// bf16, head widths of 64 or 128 (d_qk <= d_v), and a K/V head no longer than the 2 GiB buffer window.
 bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
   if (dtype != 1) return false;
-  if (p.d_qk != p.d_v) return false;
-  if (p.d_qk != 128 && p.d_qk != 64) return false;
-  return (int64_t)p.S_k * p.d_qk * 2 < (1ll << 31);
+  const bool ok = (p.d_qk == 128 && p.d_v == 128) || (p.d_qk == 64 && p.d_v == 64) || (p.d_qk == 64 && p.d_v == 128);
+  if (!ok) return false;
+  return (int64_t)p.S_k * p.d_v * 2 < (1ll << 31);
 }
 
 namespace {
 int g_prefill_waves = 8;
-template <int D, int NW>
+template <int DQK, int DV, int NW>
 hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
   constexpr int kBM = NW * 32;
   const int n_qtiles = (p.S_q + kBM - 1) / kBM;
   const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
-  prefill_mfma_kernel<D, NW><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
+  prefill_mfma_kernel<DQK, DV, NW><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
   return hipGetLastError();
 }
 }  // namespace
@@ -372,8 +372,9 @@ void set_prefill_waves(int nw) { g_prefill_waves = (nw == 4) ? 4 : 8; }
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
   const bool eight = g_prefill_waves == 8;
-  if (p.d_qk == 128) return eight ? launch_nw<128, 8>(p, s) : launch_nw<128, 4>(p, s);
-  return eight ? launch_nw<64, 8>(p, s) : launch_nw<64, 4>(p, s);
+  if (p.d_qk == 128) return eight ? launch_nw<128, 128, 8>(p, s) : launch_nw<128, 128, 4>(p, s);
+  if (p.d_v == 128) return eight ? launch_nw<64, 128, 8>(p, s) : launch_nw<64, 128, 4>(p, s);
+  return eight ? launch_nw<64, 64, 8>(p, s) : launch_nw<64, 64, 4>(p, s);
 }
 
 }  // namespace diffqkv

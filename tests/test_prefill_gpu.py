@@ -32,7 +32,7 @@ def run(cfg, causal=True, rows=None, force_generic=False):
 
 
 SHAPES = [(32, 4, 16, 128, 128), (8, 2, 4, 64, 64), (4, 4, 4, 128, 128), (8, 1, 1, 64, 64), (8, 4, 2, 64, 64),
-          (16, 2, 8, 128, 128)]
+          (16, 2, 8, 128, 128), (16, 2, 4, 64, 128), (8, 2, 2, 128, 64)]
 
 
 @pytest.mark.parametrize("shape", SHAPES)
