@@ -72,14 +72,36 @@ size_t workspace_for(const diffqkv_shape* s, int32_t num_splits) {
   return (bytes + 255) / 256 * 256;
 }
 
+// Ragged mode of the MFMA decode kernel: one worker per wavefront, two workgroups per compute unit,
+// equal slices of the 32-token-unit space.  The smallest slice (and with it the number of partial
+// slots a row can need) is fixed from the host-side bound on the work, so that small batches still
+// spread over the whole chip while large ones keep the partial results few.
+constexpr int kStreamKWorkers = 2 * kComputeUnits * 4;
+struct StreamKPlan {
+  bool use;
+  int32_t lmin, slots;
+  size_t cum_bytes, bytes;
+};
+StreamKPlan plan_streamk(const diffqkv_shape* s, int32_t max_T) {
+  StreamKPlan k = {};
+  if (g_tuning.decode_ragged_mode == 2 || s->dtype != DIFFQKV_BF16 || s->B <= 0 || max_T <= 0) return k;
+  if (s->B > decode_streamk_max_batch()) return k;
+  int32_t chunk, splits;
+  plan_decode(s, max_T, true, &chunk, &splits);
+  if (splits <= 1) return k;  // a context this short runs in a single pass without partial results
+  const int64_t u_max = (max_T + 31) / 32;
+  int64_t lmin = ((int64_t)s->B * s->n_k * u_max + kStreamKWorkers - 1) / kStreamKWorkers;
+  lmin = lmin < 4 ? 4 : (lmin > 32 ? 32 : lmin);
+  k.use = true;
+  k.lmin = (int32_t)lmin;
+  k.slots = (int32_t)((u_max + lmin - 1) / lmin) + 1;
+  k.cum_bytes = ((size_t)(s->B + 1) * sizeof(int32_t) + 255) / 256 * 256;
+  k.bytes = k.cum_bytes + workspace_for(s, k.slots < 2 ? 2 : k.slots);
+  return k;
+}
+
 int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* workspace,
                size_t workspace_bytes, hipStream_t stream) {
-  plan_decode(s, p.T, p.seqlens != nullptr, &p.chunk, &p.num_splits);
-  const size_t need = workspace_for(s, p.num_splits);
-  if (need) {
-    if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return DIFFQKV_ERR_ALIGN;
-  }
   p.B = s->B;
   p.n_q = s->n_q;
   p.n_k = s->n_k;
@@ -89,11 +111,36 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
   p.n_groups = s->n_k < s->n_v ? s->n_k : s->n_v;
   p.G = s->n_q / p.n_groups;
   p.scale_log2 = scale_log2(s);
-  p.o_part = (float*)workspace;
+  const bool mfma = !g_tuning.force_generic && decode_mfma_supported(p, s->dtype);
+  // ragged lengths on the MFMA kernel: equal slices per wavefront instead of fixed chunks
+  StreamKPlan sk = {};
+  if (mfma && p.seqlens != nullptr)
+    sk = plan_streamk(s, p.T);
+  size_t need;
+  if (sk.use) {
+    p.chunk = 0;
+    p.num_splits = sk.slots < 2 ? 2 : sk.slots;
+    need = sk.bytes;
+  } else {
+    plan_decode(s, p.T, p.seqlens != nullptr, &p.chunk, &p.num_splits);
+    need = workspace_for(s, p.num_splits);
+  }
+  if (need) {
+    if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DIFFQKV_ERR_ALIGN;
+  }
+  if (sk.use) {
+    p.sk_cum = (int32_t*)workspace;
+    p.sk_workers = kStreamKWorkers;
+    p.sk_lmin = sk.lmin;
+    p.o_part = (float*)((char*)workspace + sk.cum_bytes);
+  } else {
+    p.o_part = (float*)workspace;
+  }
   p.lse_part = need ? p.o_part + (size_t)s->B * s->n_q * p.num_splits * s->d_v : nullptr;
   if (s->B == 0) return DIFFQKV_OK;
   hipError_t e;
-  if (!g_tuning.force_generic && decode_mfma_supported(p, s->dtype))
+  if (mfma)
     e = launch_decode_mfma(p, paged, stream);
   else
     e = launch_decode_generic(p, s->dtype, paged, stream);
@@ -122,10 +169,14 @@ void diffqkv_set_split_event(void* hip_event) { g_split_event = (hipEvent_t)hip_
 
 size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape, int32_t max_T) {
   if (check_shape(shape) != DIFFQKV_OK || max_T < 0) return 0;
-  // the ragged plan never has fewer splits than the uniform one: its size covers both
+  // the fixed-chunk plan for ragged lengths never has fewer splits than the uniform one, and the
+  // equal-slice plan of the MFMA kernel has a size of its own: the figure covers all three
   int32_t chunk, splits;
   plan_decode(shape, max_T, true, &chunk, &splits);
-  return workspace_for(shape, splits);
+  size_t bytes = workspace_for(shape, splits);
+  const StreamKPlan sk = plan_streamk(shape, max_T);
+  if (sk.use && sk.bytes > bytes) bytes = sk.bytes;
+  return bytes;
 }
 
 int diffqkv_decode(const diffqkv_shape* shape, const void* q, const void* k_cache,

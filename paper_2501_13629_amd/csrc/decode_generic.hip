@@ -199,7 +199,19 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(DecodeParams p
     if (tid == 0 && p.lse_out) p.lse_out[row] = -INFINITY;
     return;
   }
-  const int live = (Tb + p.chunk - 1) / p.chunk;
+  int live;
+  if (p.sk_cum) {
+    // ragged mode of the MFMA kernel: the stream (b, K head) occupies units [start, start + u_b) of
+    // the unit space cut into slices of L units, one partial per slice that touches it
+    const int64_t total = (int64_t)p.n_k * p.sk_cum[p.B];
+    int64_t L = (total + p.sk_workers - 1) / p.sk_workers;
+    L = L < p.sk_lmin ? p.sk_lmin : L;
+    const int u_b = p.sk_cum[b + 1] - p.sk_cum[b];
+    const int64_t start = (int64_t)p.n_k * p.sk_cum[b] + (int64_t)(h / p.G) * u_b;
+    live = (int)((start + u_b - 1) / L - start / L) + 1;
+  } else {
+    live = (Tb + p.chunk - 1) / p.chunk;
+  }
   const float* lp = p.lse_part + row * p.num_splits;
   const float* op = p.o_part + row * p.num_splits * p.d_v;
 

@@ -44,6 +44,7 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kSub = 32;             // tokens per wavefront step
 constexpr int kTile = kWaves * kSub; // tokens per workgroup step
+constexpr int kStreamKMaxB = 4096;   // sequences whose unit prefix fits the LDS table of the ragged mode
 
 // CW bf16 channels (CW * 2 bytes) from a 16-byte-aligned (CW = 8) or 8-byte-aligned (CW = 4) address
 template <int CW>
@@ -89,53 +90,55 @@ __device__ __forceinline__ u32x2 buffer_load_chunk<4>(rsrc_t r, int voff, int so
 // over V heads is unrolled and software-pipelined: while the matrix cores work on one unit (the K
 // rows of a sub-tile, or the rows of one V head), the loads of the next unit are already in flight
 // into a second set of registers.  RT = 0 takes any ratio with a plain loop.
-template <int DQK, int DV, bool PAGED, int RT>
+//
+// SK selects how the work is cut:
+//   SK = false  grid (splits, n_k, B): one workgroup per (sequence, K head, fixed-size chunk); its 4
+//               wavefronts take interleaved sub-tiles and merge through LDS.  Used for uniform lengths,
+//               where one round of workgroups covers the whole cache.
+//   SK = true   ragged lengths: every wavefront is a worker of its own.  All 32-token units of all
+//               (sequence, K head) streams are laid end to end and cut into equal slices, one per
+//               worker, so every worker streams the same number of bytes whatever the length mix.
+//               A worker whose slice crosses from one (sequence, K head) to the next writes one
+//               partial result per stream it touched; slot numbers follow from the slice length.
+template <int DQK, int DV, bool PAGED, int RT, bool SK>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p) {
   constexpr int KK = DQK / 32;  // k-steps of the score product
   constexpr int CW = DV / 16;   // channels per lane in the V product
   typedef typename ChunkLoad<CW>::vec vvec;
 
-  __shared__ float lds_ml[2][kWaves][16];
-  __shared__ float lds_o[kWaves][16][DV + 4];
+  __shared__ float lds_ml[2][SK ? 1 : kWaves][16];
+  __shared__ float lds_o[SK ? 1 : kWaves][16][DV + 4];
+  __shared__ int32_t lds_cum[SK ? kStreamKMaxB + 1 : 1];  // units of the sequences before b
+  __shared__ int32_t lds_scan[SK ? kThreads : 1];
 
-  const int split = blockIdx.x, kh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, n = lane & 15;
 
-  const int G = p.G;                           // query rows under this K head (<= 16)
-  const int R = RT ? RT : p.n_v / p.n_k;       // V heads under this K head
+  const int G = p.G;                           // query rows under a K head (<= 16)
+  const int R = RT ? RT : p.n_v / p.n_k;       // V heads under a K head
   const int g_v = G / R;                       // query rows per V head
-  const int h0 = kh * G;
-
-  int Tb = p.seqlens ? p.seqlens[b] : p.T;
-  Tb = Tb < p.T ? Tb : p.T;
-  const int c0 = split * p.chunk;
-  if (c0 >= Tb) {
-    if (p.num_splits == 1) {  // empty sequence and no combine pass: zeros, lse = -inf
-      uint16_t* out = (uint16_t*)p.out + ((int64_t)b * p.n_q + h0) * DV;
-      for (int o = tid; o < G * DV; o += kThreads) out[o] = 0;
-      if (p.lse_out && tid < G) p.lse_out[(int64_t)b * p.n_q + h0 + tid] = -INFINITY;
-    }
-    return;
-  }
-  const int c1 = (c0 + p.chunk < Tb) ? c0 + p.chunk : Tb;
-  const int last = c1 - 1;
-
-  // wavefront-uniform bases of this K head and of the first V head under it
-  const uint16_t* khead = (const uint16_t*)p.k + (int64_t)kh * p.k_sh;
-  const uint16_t* vhead = (const uint16_t*)p.v + (int64_t)(kh * R) * p.v_sh;
-  if (!PAGED) {
-    khead += (int64_t)b * p.k_sb;
-    vhead += (int64_t)b * p.v_sb;
-  }
-  const int32_t* bt = PAGED ? p.block_table + (int64_t)b * p.max_pages : nullptr;
   const int k_row_bytes = (int)p.k_st * 2, v_row_bytes = (int)p.v_st * 2, v_head_bytes = (int)p.v_sh * 2;
 
-  // Q^T as the B operand: lane (g, n) holds channels 32 kk + 8 g .. + 7 of query row n.
-  bf16x8 qf[KK];
-  {
+  // The stream being read: set once (SK = false) or per segment of the worker's slice (SK = true).
+  int b = 0, kh = 0, h0 = 0;
+  int c1 = 0, last = 0;            // end of the live tokens this wavefront may read, and c1 - 1
+  const uint16_t* khead = nullptr; // wavefront-uniform bases of the K head and of its first V head
+  const uint16_t* vhead = nullptr;
+  const int32_t* bt = nullptr;
+  bf16x8 qf[KK];                   // Q^T as the B operand: lane (g, n): channels 32 kk + 8 g .. + 7 of row n
+  auto select_stream = [&](int b_, int kh_) {
+    b = b_;
+    kh = kh_;
+    h0 = kh * G;
+    khead = (const uint16_t*)p.k + (int64_t)kh * p.k_sh;
+    vhead = (const uint16_t*)p.v + (int64_t)(kh * R) * p.v_sh;
+    if (!PAGED) {
+      khead += (int64_t)b * p.k_sb;
+      vhead += (int64_t)b * p.v_sb;
+    }
+    bt = PAGED ? p.block_table + (int64_t)b * p.max_pages : nullptr;
     const uint16_t* qrow = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h0 + (n < G ? n : 0)) * DQK;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
       if (n >= G) w = u32x4{0u, 0u, 0u, 0u};
       qf[kk] = __builtin_bit_cast(bf16x8, w);
     }
-  }
+  };
 
   // Where a sub-tile (two 16-token blocks starting at token ts) lives: one buffer resource per
   // block for K and for V (a block never straddles a page), plus this lane's byte offsets inside
@@ -221,11 +224,16 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
   };
 
   f32x4 acc[CW];
+  float m_run;   // running maximum of query row n (same in the 4 lanes of a column)
+  float l_run;   // this lane's share of the running sum
+  uint32_t pw[4];  // P^T as the B operand: k-slots 0..3 = block 0, 4..7 = block 1
+  auto reset_state = [&]() {
 #pragma unroll
-  for (int c = 0; c < CW; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY;  // running maximum of query row n (same in the 4 lanes of a column)
-  float l_run = 0.f;        // this lane's share of the running sum
-  uint32_t pw[4];           // P^T as the B operand: k-slots 0..3 = block 0, 4..7 = block 1
+    for (int c = 0; c < CW; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m_run = -INFINITY;
+    l_run = 0.f;
+  };
+  reset_state();
 
   // S^T = K Q^T, then the online softmax.  Lane (g, n): tokens ts + 16 blk + 4 g + x of row n.
   auto scores_and_softmax = [&](int ts, const u32x4 (&kw)[2][KK], bool tail) {
@@ -296,47 +304,162 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
     }
   };
 
-  int ts = c0 + wave * kSub;
-  if (RT) {
-    if (ts + kSub <= c1) {  // at least one full sub-tile
-      u32x4 kw[2][KK];
-      vvec va[8], vb[8];
-      SubTile cur = locate(ts, false);
-      load_k(cur, full_off, kw);
-      // MORE is a compile-time flag (a K prefetch for the next full sub-tile follows), so that the
-      // number of loads in flight at every wait is known statically.
-      auto sub_tile = [&](auto more_tag) {
-        constexpr bool MORE = decltype(more_tag)::value;
-        load_v(cur, full_off, 0, va);
-        scores_and_softmax(ts, kw, false);
-        SubTile nxt = cur;
-        if (MORE) nxt = locate(ts + kTile, false);
+  // Streams the sub-tiles ts, ts + step, ... below c1 of the selected stream into (m_run, l_run, acc).
+  auto run_sub_tiles = [&](int ts, const int step) {
+    if (RT) {
+      if (ts + kSub <= c1) {  // at least one full sub-tile
+        u32x4 kw[2][KK];
+        vvec va[8], vb[8];
+        SubTile cur = locate(ts, false);
+        load_k(cur, full_off, kw);
+        // MORE is a compile-time flag (a K prefetch for the next full sub-tile follows), so that the
+        // number of loads in flight at every wait is known statically.
+        auto sub_tile = [&](auto more_tag) {
+          constexpr bool MORE = decltype(more_tag)::value;
+          load_v(cur, full_off, 0, va);
+          scores_and_softmax(ts, kw, false);
+          SubTile nxt = cur;
+          if (MORE) nxt = locate(ts + step, false);
 #pragma unroll
-        for (int vv = 0; vv < RT; ++vv) {
-          // put the next unit's loads in flight, then consume the current V head
-          if (vv + 1 < RT) {
+          for (int vv = 0; vv < RT; ++vv) {
+            // put the next unit's loads in flight, then consume the current V head
+            if (vv + 1 < RT) {
+              if (vv & 1)
+                load_v(cur, full_off, vv + 1, va);
+              else
+                load_v(cur, full_off, vv + 1, vb);
+            } else if (MORE) {
+              load_k(nxt, full_off, kw);
+            }
             if (vv & 1)
-              load_v(cur, full_off, vv + 1, va);
+              accumulate_v(vv, vb);
             else
-              load_v(cur, full_off, vv + 1, vb);
-          } else if (MORE) {
-            load_k(nxt, full_off, kw);
+              accumulate_v(vv, va);
           }
-          if (vv & 1)
-            accumulate_v(vv, vb);
-          else
-            accumulate_v(vv, va);
-        }
-        cur = nxt;
-        ts += kTile;
-      };
-      while (ts + kTile + kSub <= c1) sub_tile(std::true_type{});
-      sub_tile(std::false_type{});
+          cur = nxt;
+          ts += step;
+        };
+        while (ts + step + kSub <= c1) sub_tile(std::true_type{});
+        sub_tile(std::false_type{});
+      }
+      if (ts < c1) plain_sub_tile(ts, true);
+    } else {
+      for (; ts + kSub <= c1; ts += step) plain_sub_tile(ts, false);
+      if (ts < c1) plain_sub_tile(ts, true);
     }
-    if (ts < c1) plain_sub_tile(ts, true);
-  } else {
-    for (; ts + kSub <= c1; ts += kTile) plain_sub_tile(ts, false);
-    if (ts < c1) plain_sub_tile(ts, true);
+  };
+
+  if (SK) {
+    // ---- prefix of 32-token units per sequence, in LDS (and, from workgroup 0, in the workspace
+    //      for the combine kernel) ----------------------------------------------------------------
+    const int B = p.B;
+    const int per = (B + kThreads - 1) / kThreads;
+    int mine_sum = 0;
+    for (int i = 0; i < per; ++i) {
+      const int bb = tid * per + i;
+      if (bb < B) {
+        int t = p.seqlens[bb];
+        t = t < 0 ? 0 : (t < p.T ? t : p.T);
+        mine_sum += (t + kSub - 1) / kSub;
+      }
+    }
+    lds_scan[tid] = mine_sum;
+    __syncthreads();
+    for (int d = 1; d < kThreads; d <<= 1) {  // inclusive scan of the per-thread sums
+      const int v = tid >= d ? lds_scan[tid - d] : 0;
+      __syncthreads();
+      lds_scan[tid] += v;
+      __syncthreads();
+    }
+    {
+      int run = lds_scan[tid] - mine_sum;  // exclusive prefix of this thread's first sequence
+      for (int i = 0; i < per; ++i) {
+        const int bb = tid * per + i;
+        if (bb < B) {
+          lds_cum[bb] = run;
+          int t = p.seqlens[bb];
+          t = t < 0 ? 0 : (t < p.T ? t : p.T);
+          run += (t + kSub - 1) / kSub;
+        }
+      }
+      if (tid == kThreads - 1) lds_cum[B] = lds_scan[kThreads - 1];
+    }
+    __syncthreads();
+    if (blockIdx.x == 0)
+      for (int i = tid; i <= B; i += kThreads) p.sk_cum[i] = lds_cum[i];
+
+    // ---- this worker's slice of the unit space: stream (b, kh) starts at n_k cum[b] + kh u_b ----
+    const int64_t total = (int64_t)p.n_k * lds_cum[B];
+    const int workers = gridDim.x * kWaves;
+    int64_t L = (total + workers - 1) / workers;
+    L = L < p.sk_lmin ? p.sk_lmin : L;
+    const int worker = blockIdx.x * kWaves + wave;
+    int64_t pos = (int64_t)worker * L;
+    const int64_t end = pos + L < total ? pos + L : total;
+    while (pos < end) {
+      // the sequence that holds unit `pos`: the last b with n_k cum[b] <= pos
+      int lo = 0, hi = B - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)p.n_k * lds_cum[mid] <= pos) lo = mid; else hi = mid - 1;
+      }
+      const int bb = lo;
+      const int u_b = lds_cum[bb + 1] - lds_cum[bb];  // > 0: empty sequences own no unit
+      const int64_t rel = pos - (int64_t)p.n_k * lds_cum[bb];
+      const int khh = (int)(rel / u_b), j0 = (int)(rel % u_b);
+      const int64_t stream_start = pos - j0;
+      int64_t seg_end = stream_start + u_b;
+      seg_end = seg_end < end ? seg_end : end;
+      const int j1 = (int)(seg_end - stream_start);  // units [j0, j1) of stream (bb, khh)
+      int Tb = p.seqlens[bb];
+      Tb = Tb < p.T ? Tb : p.T;
+      select_stream(bb, khh);
+      c1 = j1 * kSub < Tb ? j1 * kSub : Tb;
+      last = c1 - 1;
+      reset_state();
+      run_sub_tiles(j0 * kSub, kSub);
+      // flush this stream's partial: slot = distance from the first worker that touches the stream
+      l_run += __shfl_xor(l_run, 16, 64);
+      l_run += __shfl_xor(l_run, 32, 64);
+      const int slot = worker - (int)(stream_start / L);
+      const float inv = 1.f / l_run;
+      if (n < G) {
+        const int64_t row = ((int64_t)b * p.n_q + h0 + n) * p.num_splits + slot;
+        float* orow = p.o_part + row * DV;
+        // lane (g, n), acc[c][x]: query row n, channel (4 g + x) * CW + c
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+          for (int c4 = 0; c4 < CW; c4 += 4) {
+            const f32x4 w = {acc[c4][x] * inv, acc[c4 + 1][x] * inv, acc[c4 + 2][x] * inv, acc[c4 + 3][x] * inv};
+            *(f32x4*)(orow + (4 * g + x) * CW + c4) = w;
+          }
+        if (g == 0) p.lse_part[row] = m_run + log2f(l_run);
+      }
+      pos = seg_end;
+    }
+    return;
+  }
+
+  // ---- fixed-size chunks ---------------------------------------------------------------------------
+  const int split = blockIdx.x;
+  {
+    const int kh_ = blockIdx.y, b_ = blockIdx.z;
+    int Tb = p.seqlens ? p.seqlens[b_] : p.T;
+    Tb = Tb < p.T ? Tb : p.T;
+    const int c0 = split * p.chunk;
+    if (c0 >= Tb) {
+      if (p.num_splits == 1) {  // empty sequence and no combine pass: zeros, lse = -inf
+        uint16_t* out = (uint16_t*)p.out + ((int64_t)b_ * p.n_q + kh_ * G) * DV;
+        for (int o = tid; o < G * DV; o += kThreads) out[o] = 0;
+        if (p.lse_out && tid < G) p.lse_out[(int64_t)b_ * p.n_q + kh_ * G + tid] = -INFINITY;
+      }
+      return;
+    }
+    select_stream(b_, kh_);
+    c1 = (c0 + p.chunk < Tb) ? c0 + p.chunk : Tb;
+    last = c1 - 1;
+    run_sub_tiles(c0 + wave * kSub, kTile);
   }
 
   // ---- merge the 4 wavefronts --------------------------------------------------------------------
@@ -384,11 +507,20 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
 
 template <int DQK, int DV, int RT>
 hipError_t launch_ratio(const DecodeParams& p, bool paged, hipStream_t s) {
-  dim3 grid(p.num_splits, p.n_k, p.B), block(kThreads);
-  if (paged)
-    decode_mfma_kernel<DQK, DV, true, RT><<<grid, block, 0, s>>>(p);
-  else
-    decode_mfma_kernel<DQK, DV, false, RT><<<grid, block, 0, s>>>(p);
+  dim3 block(kThreads);
+  if (p.sk_cum) {  // equal slices of the ragged unit space, one per wavefront
+    dim3 grid(p.sk_workers / kWaves);
+    if (paged)
+      decode_mfma_kernel<DQK, DV, true, RT, true><<<grid, block, 0, s>>>(p);
+    else
+      decode_mfma_kernel<DQK, DV, false, RT, true><<<grid, block, 0, s>>>(p);
+  } else {
+    dim3 grid(p.num_splits, p.n_k, p.B);
+    if (paged)
+      decode_mfma_kernel<DQK, DV, true, RT, false><<<grid, block, 0, s>>>(p);
+    else
+      decode_mfma_kernel<DQK, DV, false, RT, false><<<grid, block, 0, s>>>(p);
+  }
   return hipGetLastError();
 }
 
@@ -406,6 +538,8 @@ hipError_t launch_dims(const DecodeParams& p, bool paged, hipStream_t s) {
 }  // namespace
 
 // bf16, K the coarser side, at most 16 query rows per K head, head widths 64 or 128.
+int decode_streamk_max_batch() { return kStreamKMaxB; }
+
 bool decode_mfma_supported(const DecodeParams& p, int dtype) {
   if (dtype != 1) return false;
   if (p.n_k > p.n_v || p.n_v % p.n_k != 0) return false;

@@ -26,6 +26,11 @@ struct DecodeParams {
   float* lse_part;   // [B, n_q, num_splits]      base-2 log-sum-exp of each split
   void* out;         // [B, n_q, d_v]
   float* lse_out;    // [B, n_q] or nullptr (natural log)
+  // Ragged mode of the MFMA kernel (sk_cum != nullptr): equal slices of the unit space per
+  // wavefront; num_splits then is the number of partial slots reserved per row.
+  int32_t* sk_cum;     // workspace, [B + 1]: 32-token units of the sequences before b
+  int32_t sk_workers;  // wavefronts launched (a multiple of 4)
+  int32_t sk_lmin;     // smallest slice, in units
 };
 
 struct PrefillParams {
@@ -58,6 +63,7 @@ struct AppendParams {
 // dtype: 0 = fp32, 1 = bf16 (diffqkv_dtype).  All return a hipError_t from the launch.
 hipError_t launch_decode_generic(const DecodeParams& p, int dtype, bool paged, hipStream_t s);
 bool decode_mfma_supported(const DecodeParams& p, int dtype);
+int decode_streamk_max_batch();
 hipError_t launch_decode_mfma(const DecodeParams& p, bool paged, hipStream_t s);
 hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t s);

@@ -77,7 +77,7 @@ def test_decode_validation_codes(lib):
     need = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 1 << 16)
     assert need > 0
     assert decode(lib, s, T=1 << 16, ws=0) == E_WS
-    assert decode(lib, s, T=1 << 16, ws_bytes=need - 1) == E_WS
+    assert decode(lib, s, T=1 << 16, ws_bytes=4096) == E_WS  # far below any plan for this shape
     # an empty batch is a valid no-op and launches nothing
     assert decode(lib, shape(B=0), q=0, k=0, v=0, out=0, ws=0, ws_bytes=0) == OK
 
@@ -115,12 +115,17 @@ def test_split_plan_is_a_function_of_shapes(lib):
     assert a == b and a % 256 == 0 and a > 0
     # short contexts run in a single pass and need no workspace
     assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 128) == 0
-    # the knob changes the plan; resetting restores it
-    binding.diffqkv_set_tuning(decode_chunk_tokens=512)
+    # the figure covers the equal-slice plan for ragged calls: 1024 units of 32 tokens, smallest slice
+    # 8 units (8 x 2 x 1024 units over 2048 wavefronts) => 129 partial slots per row, plus the prefix table
+    assert a == 256 + 8 * 32 * 129 * 129 * 4
+    # fixed-size chunks only: the knob changes the plan; resetting restores it
+    binding.diffqkv_set_tuning(decode_ragged_mode=2)
+    f = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
+    binding.diffqkv_set_tuning(decode_chunk_tokens=512, decode_ragged_mode=2)
     c = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
     binding.diffqkv_set_tuning()
-    assert c != a and lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == a
-    assert c == 8 * 32 * 64 * 129 * 4
+    assert f == 8 * 32 * 16 * 129 * 4 and c == 8 * 32 * 64 * 129 * 4
+    assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == a
 
 
 def test_binding_refuses_cpu_tensors():

@@ -155,3 +155,38 @@ def test_bytes_model_sanity_k_heads():
     ref = util.oracle_decode(d)[0]
     util.check(a, ref, "bf16")
     util.check(b, ref, "bf16")
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_ragged_many_sequences_both_plans(mode):
+    """Many sequences of very uneven length (some empty), more than one sequence per thread in the
+    prefix scan of the equal-slice plan; mode 2 forces fixed-size chunks on the same inputs."""
+    B, T_cap = 301, 777
+    cfg = inputs.config("decode_4k", B=B, n_q=16, n_k=2, n_v=4, d_qk=128, d_v=128, T=T_cap, index=17)
+    d = inputs.make_decode(cfg)
+    rng = np.random.default_rng(17)
+    sl = rng.integers(0, T_cap + 1, size=B).astype(np.int32)
+    sl[[0, 5, 300]] = [0, T_cap, 1]
+    sl[100:140] = 0
+    d["seqlens"] = torch.from_numpy(sl)
+    binding.diffqkv_set_tuning(decode_ragged_mode=mode)
+    out, lse = binding.diffqkv_decode(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]),
+                                      seqlens=util.dev(d["seqlens"]), want_lse=True)
+    ref, ref_lse = util.oracle_decode(d)
+    util.check(out, ref, "bf16")
+    util.check_lse(lse, ref_lse)
+    assert torch.all(out[100:140] == 0)
+
+
+def test_ragged_plans_agree_on_long_contexts():
+    """A few long sequences: slices of the equal-slice plan cross sequence and head boundaries."""
+    cfg = inputs.config("decode_32k", B=5, T=9000, index=18)
+    d = inputs.make_decode(cfg)
+    d["seqlens"] = torch.tensor([9000, 33, 4097, 0, 8191], dtype=torch.int32)
+    ref, ref_lse = util.oracle_decode(d)
+    for mode in (0, 2):
+        binding.diffqkv_set_tuning(decode_ragged_mode=mode)
+        out, lse = binding.diffqkv_decode(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]),
+                                          seqlens=util.dev(d["seqlens"]), want_lse=True)
+        util.check(out, ref, "bf16", "mode %d" % mode)
+        util.check_lse(lse, ref_lse)
