@@ -74,9 +74,11 @@ typedef struct {
   int32_t decode_chunk_tokens; /* tokens per context split (multiple of 128)                      */
   int32_t force_generic;       /* 1: always take the portable kernels instead of the MFMA ones    */
   int32_t prefill_waves;       /* wavefronts per workgroup in the MFMA prefill: 4 or 8           */
-  int32_t decode_ragged_mode;  /* calls with seqlens on the MFMA kernel: 0 equal slices per
-                                  wavefront (default), 2 fixed-size chunks                       */
-  int32_t reserved[4];
+  int32_t decode_ragged_mode;  /* work split of the MFMA decode kernel.  0: equal slices per
+                                  wavefront when seqlens is given, fixed-size chunks otherwise;
+                                  1: equal slices always; 2: fixed-size chunks always            */
+  int32_t decode_workers;      /* wavefronts launched by the equal-slice split (multiple of 4)   */
+  int32_t reserved[3];
 } diffqkv_tuning;
 void diffqkv_set_tuning(const diffqkv_tuning* t /* host; NULL resets */);
 

@@ -35,7 +35,7 @@ class Shape(ctypes.Structure):
 class Tuning(ctypes.Structure):
     _fields_ = [("decode_chunk_tokens", ctypes.c_int32), ("force_generic", ctypes.c_int32),
                 ("prefill_waves", ctypes.c_int32), ("decode_ragged_mode", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 4)]
+                ("decode_workers", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class DiffQKVError(RuntimeError):
@@ -122,8 +122,9 @@ def _shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, scale) -> Shape:
 
 
 def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False, prefill_waves: int = 0,
-                       decode_ragged_mode: int = 0):
-    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0, int(prefill_waves), int(decode_ragged_mode))
+                       decode_ragged_mode: int = 0, decode_workers: int = 0):
+    t = Tuning(int(decode_chunk_tokens), 1 if force_generic else 0, int(prefill_waves), int(decode_ragged_mode),
+               int(decode_workers))
     load_library().diffqkv_set_tuning(ctypes.byref(t))
 
 

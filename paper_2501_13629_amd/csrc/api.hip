@@ -77,6 +77,9 @@ size_t workspace_for(const diffqkv_shape* s, int32_t num_splits) {
 // slots a row can need) is fixed from the host-side bound on the work, so that small batches still
 // spread over the whole chip while large ones keep the partial results few.
 constexpr int kStreamKWorkers = 2 * kComputeUnits * 4;
+int streamk_workers() {
+  return g_tuning.decode_workers > 0 ? (g_tuning.decode_workers + 3) / 4 * 4 : kStreamKWorkers;
+}
 struct StreamKPlan {
   bool use;
   int32_t lmin, slots;
@@ -90,7 +93,7 @@ StreamKPlan plan_streamk(const diffqkv_shape* s, int32_t max_T) {
   plan_decode(s, max_T, true, &chunk, &splits);
   if (splits <= 1) return k;  // a context this short runs in a single pass without partial results
   const int64_t u_max = (max_T + 31) / 32;
-  int64_t lmin = ((int64_t)s->B * s->n_k * u_max + kStreamKWorkers - 1) / kStreamKWorkers;
+  int64_t lmin = ((int64_t)s->B * s->n_k * u_max + streamk_workers() - 1) / streamk_workers();
   lmin = lmin < 4 ? 4 : (lmin > 32 ? 32 : lmin);
   k.use = true;
   k.lmin = (int32_t)lmin;
@@ -114,8 +117,7 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
   const bool mfma = !g_tuning.force_generic && decode_mfma_supported(p, s->dtype);
   // ragged lengths on the MFMA kernel: equal slices per wavefront instead of fixed chunks
   StreamKPlan sk = {};
-  if (mfma && p.seqlens != nullptr)
-    sk = plan_streamk(s, p.T);
+  if (mfma && (p.seqlens != nullptr || g_tuning.decode_ragged_mode == 1)) sk = plan_streamk(s, p.T);
   size_t need;
   if (sk.use) {
     p.chunk = 0;
@@ -131,7 +133,7 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
   }
   if (sk.use) {
     p.sk_cum = (int32_t*)workspace;
-    p.sk_workers = kStreamKWorkers;
+    p.sk_workers = streamk_workers();
     p.sk_lmin = sk.lmin;
     p.o_part = (float*)((char*)workspace + sk.cum_bytes);
   } else {

@@ -358,7 +358,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
     for (int i = 0; i < per; ++i) {
       const int bb = tid * per + i;
       if (bb < B) {
-        int t = p.seqlens[bb];
+        int t = p.seqlens ? p.seqlens[bb] : p.T;
         t = t < 0 ? 0 : (t < p.T ? t : p.T);
         mine_sum += (t + kSub - 1) / kSub;
       }
@@ -377,7 +377,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
         const int bb = tid * per + i;
         if (bb < B) {
           lds_cum[bb] = run;
-          int t = p.seqlens[bb];
+          int t = p.seqlens ? p.seqlens[bb] : p.T;
           t = t < 0 ? 0 : (t < p.T ? t : p.T);
           run += (t + kSub - 1) / kSub;
         }
@@ -411,7 +411,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(DecodeParams p
       int64_t seg_end = stream_start + u_b;
       seg_end = seg_end < end ? seg_end : end;
       const int j1 = (int)(seg_end - stream_start);  // units [j0, j1) of stream (bb, khh)
-      int Tb = p.seqlens[bb];
+      int Tb = p.seqlens ? p.seqlens[bb] : p.T;
       Tb = Tb < p.T ? Tb : p.T;
       select_stream(bb, khh);
       c1 = j1 * kSub < Tb ? j1 * kSub : Tb;
