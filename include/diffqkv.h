@@ -143,6 +143,44 @@ int diffqkv_prefill(const diffqkv_shape* shape /* host */, const void* q, const 
                     float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Decode with selective V-cache fetching (appendix "Selective V Cache Fetching"; LoadCacheV in the
+ * formulation of section 2).  The attention weights alpha are the softmax over all T_b positions
+ * (the whole K cache is read), but only the V rows of the `top_k` previous positions with the
+ * largest weights are fetched; the current token's row (position T_b - 1) always takes part:
+ *
+ *     out[b,h,:] = sum over j in top_k(alpha[0 .. T_b-2]) and j = T_b-1 of alpha_j V[b,vh,j,:]
+ *
+ * Ties between equal scores go to the lower position.  The formula keeps alpha as it is; with
+ * renormalize != 0 the result is divided by the sum of the selected weights.  With
+ * top_k >= T_b - 1 the call equals diffqkv_decode.  An approximation by design: the paper reports
+ * top_k = 100.
+ *
+ *   arguments as in diffqkv_decode / diffqkv_decode_paged, plus
+ *   top_k        0 .. 512
+ *   sel_out      int32 [B, n_q, top_k + 1] on the device or NULL: the selected positions of every
+ *                query head (unordered, unused entries -1)
+ *   workspace    at least diffqkv_decode_topk_workspace_bytes(shape, T) bytes (fp32 scores
+ *                [B, n_q, T rounded up to 128]); for the paged call T = max_pages * page_size
+ * The selection is made on the kernel's fp32 scores (bf16 products accumulated in fp32): two
+ * positions whose scores differ by less than that arithmetic's rounding may swap places relative
+ * to an exact evaluation.
+ */
+size_t diffqkv_decode_topk_workspace_bytes(const diffqkv_shape* shape /* host */, int32_t max_T);
+int diffqkv_decode_topk(const diffqkv_shape* shape /* host */, const void* q, const void* k_cache,
+                        const void* v_cache, int64_t k_stride_b, int64_t k_stride_h,
+                        int64_t k_stride_t, int64_t v_stride_b, int64_t v_stride_h,
+                        int64_t v_stride_t, const int32_t* seqlens, int32_t T, int32_t top_k,
+                        int32_t renormalize, void* out, float* lse_out, int32_t* sel_out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+int diffqkv_decode_topk_paged(const diffqkv_shape* shape /* host */, const void* q, const void* k_pool,
+                              const void* v_pool, int64_t k_stride_page, int64_t k_stride_h,
+                              int64_t k_stride_t, int64_t v_stride_page, int64_t v_stride_h,
+                              int64_t v_stride_t, const int32_t* block_table, int32_t max_pages,
+                              int32_t page_size, const int32_t* seqlens, int32_t top_k,
+                              int32_t renormalize, void* out, float* lse_out, int32_t* sel_out,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * KV-cache append (section 3.2, "KV Cache": the store side of the cache; K and V are separate
  * tensors with their own head counts -- "differential management of KV cache").  For every sequence
  * b, copies k_new[b] into token row positions[b] of the K cache and v_new[b] into the same row of

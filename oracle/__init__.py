@@ -55,6 +55,8 @@ def _load():
         lib.oracle_prefill.argtypes = [i32] * 7 + [f64] + [vp] * 3 + [i32, i32, i32, vp, i32, vp, vp]
         lib.oracle_lse_merge.restype = i32
         lib.oracle_lse_merge.argtypes = [i32, i32, vp, vp, vp, vp]
+        lib.oracle_decode_topk.restype = i32
+        lib.oracle_decode_topk.argtypes = [i32] * 7 + [f64] + [vp] * 3 + [i64] * 6 + [vp, i32, i32, i32, vp, vp, vp]
         lib.oracle_num_threads.restype = i32
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -117,6 +119,37 @@ def decode(q, k_cache, v_cache, seqlens=None, scale=None, T=None):
     if rc != 0:
         raise ValueError("oracle_decode rejected its arguments")
     return out, lse
+
+
+def decode_topk(q, k_cache, v_cache, top_k, seqlens=None, scale=None, T=None, renormalize=False):
+    """Selective V-cache fetching: weights from the softmax over all T positions, output from the
+    `top_k` previous positions of largest weight plus the current token (position T_b - 1).
+    Returns (out [B,n_q,d_v], lse [B,n_q], selected int32 [B,n_q,top_k+1] padded with -1)."""
+    code = _dtype_code(q)
+    assert _dtype_code(k_cache) == code and _dtype_code(v_cache) == code
+    q = np.ascontiguousarray(q)
+    B, n_q, d_qk = q.shape
+    _, n_k, T_cap, _ = k_cache.shape
+    _, n_v, _, d_v = v_cache.shape
+    ks, vs = _elem_strides(k_cache), _elem_strides(v_cache)
+    assert ks[3] == 1 and vs[3] == 1
+    if T is None:
+        T = T_cap
+    if seqlens is not None:
+        seqlens = np.ascontiguousarray(seqlens, dtype=np.int32)
+    if scale is None:
+        scale = default_scale(d_qk)
+    out = np.empty((B, n_q, d_v), dtype=np.float64)
+    lse = np.empty((B, n_q), dtype=np.float64)
+    sel = np.empty((B, n_q, top_k + 1), dtype=np.int32)
+    rc = _load().oracle_decode_topk(
+        code, B, n_q, n_k, n_v, d_qk, d_v, float(scale), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+        ks[0], ks[1], ks[2], vs[0], vs[1], vs[2], _ptr(seqlens), int(T), int(top_k), 1 if renormalize else 0,
+        _ptr(out), _ptr(lse), _ptr(sel),
+    )
+    if rc != 0:
+        raise ValueError("oracle_decode_topk rejected its arguments")
+    return out, lse, sel
 
 
 def decode_paged(q, k_pool, v_pool, block_table, seqlens, scale=None):

@@ -298,6 +298,104 @@ int oracle_lse_merge(int S, int d_v, const double* o_parts, const double* lse_pa
   return 0;
 }
 
+
+/*
+ * Selective V-cache fetching (appendix "Selective V Cache Fetching"; LoadCacheV in section 2):
+ * the attention weights alpha are the softmax over ALL T positions (the whole K cache is read);
+ * of the V cache only the rows of the `top_k` previous positions with the largest weights are
+ * loaded; the current token's row (position T-1, not yet "previous") always takes part:
+ *     V_t = [LoadCacheV(V_cache, alpha); v_t],     o = sum over the loaded rows of alpha_j V_j.
+ * Ties between equal weights go to the lower position.  The formula keeps alpha as it is
+ * (renormalize = 0); with renormalize != 0 the result is divided by the sum of the selected
+ * weights (softmax restricted to the selected set).  With top_k >= T-1 this is plain attention.
+ *   sel_out: optional int32 [B, n_q, top_k + 1]: the selected positions in increasing order,
+ *            padded with -1.
+ */
+typedef struct {
+  double w;
+  int32_t j;
+} ranked;
+static int ranked_cmp(const void* a, const void* b) {
+  const ranked* x = (const ranked*)a;
+  const ranked* y = (const ranked*)b;
+  if (x->w > y->w) return -1;
+  if (x->w < y->w) return 1;
+  return (x->j > y->j) - (x->j < y->j);
+}
+static int int_cmp(const void* a, const void* b) {
+  return (*(const int32_t*)a > *(const int32_t*)b) - (*(const int32_t*)a < *(const int32_t*)b);
+}
+
+int oracle_decode_topk(int dtype, int B, int n_q, int n_k, int n_v, int d_qk, int d_v, double scale,
+                       const void* q, const void* k_cache, const void* v_cache, int64_t k_sb,
+                       int64_t k_sh, int64_t k_st, int64_t v_sb, int64_t v_sh, int64_t v_st,
+                       const int32_t* seqlens, int T, int top_k, int renormalize, double* out,
+                       double* lse, int32_t* sel_out) {
+  if (B < 0 || n_q <= 0 || n_k <= 0 || n_v <= 0 || d_qk <= 0 || d_v <= 0 || T < 0 || top_k < 0)
+    return -1;
+  if (n_q % n_k || n_q % n_v) return -1;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < n_q; ++h) {
+      int Tb = seqlens ? seqlens[b] : T;
+      if (Tb > T) Tb = T;
+      double* o = out + ((int64_t)b * n_q + h) * d_v;
+      int32_t* sel = sel_out ? sel_out + ((int64_t)b * n_q + h) * (top_k + 1) : NULL;
+      for (int e = 0; e < d_v; ++e) o[e] = 0.0;
+      if (sel)
+        for (int i = 0; i <= top_k; ++i) sel[i] = -1;
+      if (Tb <= 0) {
+        if (lse) lse[(int64_t)b * n_q + h] = -INFINITY;
+        continue;
+      }
+      const int64_t kb = (int64_t)b * k_sb + (int64_t)shared_head(h, n_k, n_q) * k_sh;
+      const int64_t vb = (int64_t)b * v_sb + (int64_t)shared_head(h, n_v, n_q) * v_sh;
+      double* s = (double*)malloc(sizeof(double) * (size_t)Tb);
+      ranked* r = (ranked*)malloc(sizeof(ranked) * (size_t)Tb);
+      int32_t* chosen = (int32_t*)malloc(sizeof(int32_t) * (size_t)(top_k + 1));
+      if (!s || !r || !chosen) return -1;
+      double m = -INFINITY;
+      for (int j = 0; j < Tb; ++j) {
+        double dot = 0.0;
+        for (int c = 0; c < d_qk; ++c)
+          dot += load_elem(q, dtype, ((int64_t)b * n_q + h) * d_qk + c) *
+                 load_elem(k_cache, dtype, kb + (int64_t)j * k_st + c);
+        s[j] = scale * dot;
+        if (s[j] > m) m = s[j];
+      }
+      double l = 0.0;
+      for (int j = 0; j < Tb; ++j) {
+        s[j] = exp(s[j] - m);
+        l += s[j];
+      }
+      for (int j = 0; j < Tb; ++j) s[j] /= l; /* alpha */
+      /* rank the previous positions 0 .. Tb-2 by weight, ties to the lower position */
+      const int prev = Tb - 1;
+      for (int j = 0; j < prev; ++j) {
+        r[j].w = s[j];
+        r[j].j = j;
+      }
+      qsort(r, (size_t)prev, sizeof(ranked), ranked_cmp);
+      int n_sel = prev < top_k ? prev : top_k;
+      for (int i = 0; i < n_sel; ++i) chosen[i] = r[i].j;
+      chosen[n_sel++] = Tb - 1; /* the current token */
+      qsort(chosen, (size_t)n_sel, sizeof(int32_t), int_cmp);
+      double mass = 0.0;
+      for (int i = 0; i < n_sel; ++i) {
+        const int j = chosen[i];
+        mass += s[j];
+        for (int e = 0; e < d_v; ++e) o[e] += s[j] * load_elem(v_cache, dtype, vb + (int64_t)j * v_st + e);
+        if (sel) sel[i] = j;
+      }
+      if (renormalize)
+        for (int e = 0; e < d_v; ++e) o[e] /= mass;
+      if (lse) lse[(int64_t)b * n_q + h] = m + log(l);
+      free(s);
+      free(r);
+      free(chosen);
+    }
+  return 0;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int oracle_num_threads(void) { return omp_get_max_threads(); }

@@ -23,6 +23,7 @@ EXPORTS = (
     "diffqkv_set_tuning", "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_paged",
     "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_probe_stream_read", "diffqkv_strerror",
     "diffqkv_version", "diffqkv_set_split_event", "diffqkv_append", "diffqkv_append_paged",
+    "diffqkv_decode_topk_workspace_bytes", "diffqkv_decode_topk", "diffqkv_decode_topk_paged",
 )
 
 
@@ -74,6 +75,13 @@ def load_library() -> ctypes.CDLL:
     lib.diffqkv_prefill_workspace_bytes.argtypes = [sp, i32, i32]
     lib.diffqkv_prefill.restype = ctypes.c_int
     lib.diffqkv_prefill.argtypes = [sp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.diffqkv_decode_topk_workspace_bytes.restype = sz
+    lib.diffqkv_decode_topk_workspace_bytes.argtypes = [sp, i32]
+    lib.diffqkv_decode_topk.restype = ctypes.c_int
+    lib.diffqkv_decode_topk.argtypes = [sp, vp, vp, vp] + [i64] * 6 + [vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.diffqkv_decode_topk_paged.restype = ctypes.c_int
+    lib.diffqkv_decode_topk_paged.argtypes = ([sp, vp, vp, vp] + [i64] * 6 +
+                                              [vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp])
     lib.diffqkv_append.restype = ctypes.c_int
     lib.diffqkv_append.argtypes = [sp, vp, vp, vp, vp] + [i64] * 6 + [vp, i32, vp, vp]
     lib.diffqkv_append_paged.restype = ctypes.c_int
@@ -239,6 +247,74 @@ def diffqkv_prefill(q, k, v, causal=True, scale=None, out=None, lse_out=None, wa
         ctypes.byref(s), _ptr(q), _ptr(k), _ptr(v), int(S_q), int(S_k), 1 if causal else 0, _ptr(out),
         _ptr(lse_out), None, 0, _stream(q)))
     return (out, lse_out) if (want_lse or lse_out is not None) else out
+
+
+def diffqkv_decode_topk(q, k_cache, v_cache, top_k, seqlens=None, T=None, scale=None, renormalize=False, out=None,
+                        workspace=None, want_lse=False, want_selection=False):
+    """Decode with selective V fetching: softmax over all positions, output from the top_k previous
+    positions of largest weight plus the current token.  Returns out[, lse][, selection]."""
+    _dev(q, k_cache, v_cache, seqlens, out, workspace)
+    dt = _dtype_code(q)
+    if _dtype_code(k_cache) != dt or _dtype_code(v_cache) != dt:
+        raise TypeError("q, k_cache and v_cache must share a dtype")
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    B, n_q, d_qk = q.shape
+    _, n_k, T_cap, _ = k_cache.shape
+    _, n_v, _, d_v = v_cache.shape
+    if T is None:
+        T = T_cap
+    if T > T_cap:
+        raise ValueError("T exceeds the cache capacity")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or not seqlens.is_contiguous()):
+        raise TypeError("seqlens must be a contiguous int32 tensor")
+    if out is None:
+        out = torch.empty((B, n_q, d_v), dtype=q.dtype, device=q.device)
+    lse = torch.empty((B, n_q), dtype=torch.float32, device=q.device) if want_lse else None
+    sel = torch.empty((B, n_q, top_k + 1), dtype=torch.int32, device=q.device) if want_selection else None
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, scale)
+    lib = load_library()
+    need = int(lib.diffqkv_decode_topk_workspace_bytes(ctypes.byref(s), int(T)))
+    workspace = _workspace(need, q, workspace)
+    ks, vs = k_cache.stride(), v_cache.stride()
+    _check(lib.diffqkv_decode_topk(
+        ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
+        _ptr(seqlens), int(T), int(top_k), 1 if renormalize else 0, _ptr(out), _ptr(lse), _ptr(sel),
+        _ptr(workspace), workspace.numel(), _stream(q)))
+    res = [out] + ([lse] if want_lse else []) + ([sel] if want_selection else [])
+    return res[0] if len(res) == 1 else tuple(res)
+
+
+def diffqkv_decode_topk_paged(q, k_pool, v_pool, block_table, seqlens, top_k, scale=None, renormalize=False,
+                              out=None, workspace=None, want_lse=False, want_selection=False):
+    """Paged variant of diffqkv_decode_topk."""
+    _dev(q, k_pool, v_pool, block_table, seqlens, out, workspace)
+    dt = _dtype_code(q)
+    if _dtype_code(k_pool) != dt or _dtype_code(v_pool) != dt:
+        raise TypeError("q, k_pool and v_pool must share a dtype")
+    if not q.is_contiguous() or not block_table.is_contiguous() or not seqlens.is_contiguous():
+        raise ValueError("q, block_table and seqlens must be contiguous")
+    if block_table.dtype != torch.int32 or seqlens.dtype != torch.int32:
+        raise TypeError("block_table and seqlens must be int32")
+    B, n_q, d_qk = q.shape
+    _, n_k, P, _ = k_pool.shape
+    _, n_v, _, d_v = v_pool.shape
+    max_pages = block_table.shape[1]
+    if out is None:
+        out = torch.empty((B, n_q, d_v), dtype=q.dtype, device=q.device)
+    lse = torch.empty((B, n_q), dtype=torch.float32, device=q.device) if want_lse else None
+    sel = torch.empty((B, n_q, top_k + 1), dtype=torch.int32, device=q.device) if want_selection else None
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, scale)
+    lib = load_library()
+    need = int(lib.diffqkv_decode_topk_workspace_bytes(ctypes.byref(s), int(max_pages * P)))
+    workspace = _workspace(need, q, workspace)
+    ks, vs = k_pool.stride(), v_pool.stride()
+    _check(lib.diffqkv_decode_topk_paged(
+        ctypes.byref(s), _ptr(q), _ptr(k_pool), _ptr(v_pool), ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
+        _ptr(block_table), int(max_pages), int(P), _ptr(seqlens), int(top_k), 1 if renormalize else 0, _ptr(out),
+        _ptr(lse), _ptr(sel), _ptr(workspace), workspace.numel(), _stream(q)))
+    res = [out] + ([lse] if want_lse else []) + ([sel] if want_selection else [])
+    return res[0] if len(res) == 1 else tuple(res)
 
 
 def diffqkv_append(k_new, v_new, k_cache, v_cache, positions, seqlens_out=None):

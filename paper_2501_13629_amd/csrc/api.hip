@@ -258,6 +258,120 @@ int diffqkv_decode_paged(const diffqkv_shape* shape, const void* q, const void* 
   return run_decode(shape, p, true, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
+static int32_t topk_row(int32_t max_T) { return (max_T + 127) / 128 * 128; }
+
+size_t diffqkv_decode_topk_workspace_bytes(const diffqkv_shape* shape, int32_t max_T) {
+  if (check_shape(shape) != DIFFQKV_OK || max_T < 0) return 0;
+  const size_t bytes = (size_t)shape->B * shape->n_q * topk_row(max_T) * sizeof(float);
+  return (bytes + 255) / 256 * 256;
+}
+
+static int run_topk(const diffqkv_shape* shape, TopkParams& p, bool paged, int32_t top_k, int32_t renormalize,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (top_k < 0 || top_k > topk_max_k()) return DIFFQKV_ERR_SHAPE;
+  const int hi = shape->n_k > shape->n_v ? shape->n_k : shape->n_v;
+  (void)hi;
+  const size_t need = diffqkv_decode_topk_workspace_bytes(shape, p.T);
+  if (need) {
+    if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DIFFQKV_ERR_ALIGN;
+  }
+  p.T_pad = topk_row(p.T);
+  p.B = shape->B;
+  p.n_q = shape->n_q;
+  p.n_k = shape->n_k;
+  p.n_v = shape->n_v;
+  p.d_qk = shape->d_qk;
+  p.d_v = shape->d_v;
+  p.top_k = top_k;
+  p.renormalize = renormalize ? 1 : 0;
+  p.chunk = 1024;
+  p.scale_log2 = scale_log2(shape);
+  p.scores = (float*)workspace;
+  if (shape->B == 0) return DIFFQKV_OK;
+  const bool mfma = !g_tuning.force_generic && topk_scores_mfma_supported(p, shape->dtype);
+  return launch_topk(p, shape->dtype, paged, mfma, (hipStream_t)hip_stream) == hipSuccess ? DIFFQKV_OK
+                                                                                             : DIFFQKV_ERR_HIP;
+}
+
+int diffqkv_decode_topk(const diffqkv_shape* shape, const void* q, const void* k_cache, const void* v_cache,
+                        int64_t k_stride_b, int64_t k_stride_h, int64_t k_stride_t, int64_t v_stride_b,
+                        int64_t v_stride_h, int64_t v_stride_t, const int32_t* seqlens, int32_t T,
+                        int32_t top_k, int32_t renormalize, void* out, float* lse_out, int32_t* sel_out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (T < 0) return DIFFQKV_ERR_SHAPE;
+  if (shape->B > 0) {
+    if (!q || !out) return DIFFQKV_ERR_NULL;
+    if (T > 0 && (!k_cache || !v_cache)) return DIFFQKV_ERR_NULL;
+  }
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return DIFFQKV_ERR_ALIGN;
+  const int dt = shape->dtype;
+  if (!stride_ok(k_stride_b, dt) || !stride_ok(k_stride_h, dt) || !stride_ok(k_stride_t, dt) ||
+      !stride_ok(v_stride_b, dt) || !stride_ok(v_stride_h, dt) || !stride_ok(v_stride_t, dt))
+    return DIFFQKV_ERR_ALIGN;
+  if (k_stride_t < shape->d_qk || v_stride_t < shape->d_v) return DIFFQKV_ERR_SHAPE;
+  TopkParams p = {};
+  p.q = q;
+  p.k = k_cache;
+  p.v = v_cache;
+  p.k_sb = k_stride_b;
+  p.k_sh = k_stride_h;
+  p.k_st = k_stride_t;
+  p.v_sb = v_stride_b;
+  p.v_sh = v_stride_h;
+  p.v_st = v_stride_t;
+  p.seqlens = seqlens;
+  p.T = T;
+  p.out = out;
+  p.lse_out = lse_out;
+  p.sel_out = sel_out;
+  return run_topk(shape, p, false, top_k, renormalize, workspace, workspace_bytes, hip_stream);
+}
+
+int diffqkv_decode_topk_paged(const diffqkv_shape* shape, const void* q, const void* k_pool, const void* v_pool,
+                              int64_t k_stride_page, int64_t k_stride_h, int64_t k_stride_t,
+                              int64_t v_stride_page, int64_t v_stride_h, int64_t v_stride_t,
+                              const int32_t* block_table, int32_t max_pages, int32_t page_size,
+                              const int32_t* seqlens, int32_t top_k, int32_t renormalize, void* out,
+                              float* lse_out, int32_t* sel_out, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (max_pages < 0 || page_size <= 0) return DIFFQKV_ERR_SHAPE;
+  if ((int64_t)max_pages * page_size > INT32_MAX) return DIFFQKV_ERR_SHAPE;
+  if (shape->B > 0) {
+    if (!q || !out || !seqlens) return DIFFQKV_ERR_NULL;
+    if (max_pages > 0 && (!k_pool || !v_pool || !block_table)) return DIFFQKV_ERR_NULL;
+  }
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out)) return DIFFQKV_ERR_ALIGN;
+  const int dt = shape->dtype;
+  if (!stride_ok(k_stride_page, dt) || !stride_ok(k_stride_h, dt) || !stride_ok(k_stride_t, dt) ||
+      !stride_ok(v_stride_page, dt) || !stride_ok(v_stride_h, dt) || !stride_ok(v_stride_t, dt))
+    return DIFFQKV_ERR_ALIGN;
+  if (k_stride_t < shape->d_qk || v_stride_t < shape->d_v) return DIFFQKV_ERR_SHAPE;
+  TopkParams p = {};
+  p.q = q;
+  p.k = k_pool;
+  p.v = v_pool;
+  p.k_sb = k_stride_page;
+  p.k_sh = k_stride_h;
+  p.k_st = k_stride_t;
+  p.v_sb = v_stride_page;
+  p.v_sh = v_stride_h;
+  p.v_st = v_stride_t;
+  p.seqlens = seqlens;
+  p.block_table = block_table;
+  p.max_pages = max_pages;
+  p.page_size = page_size;
+  p.T = max_pages * page_size;
+  p.out = out;
+  p.lse_out = lse_out;
+  p.sel_out = sel_out;
+  return run_topk(shape, p, true, top_k, renormalize, workspace, workspace_bytes, hip_stream);
+}
+
 static int run_append(const diffqkv_shape* shape, const void* k_new, const void* v_new, void* k, void* v,
                       int64_t k_s0, int64_t k_sh, int64_t k_st, int64_t v_s0, int64_t v_sh, int64_t v_st,
                       const int32_t* block_table, int32_t max_pages, int32_t page_size,

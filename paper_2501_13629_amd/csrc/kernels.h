@@ -60,6 +60,27 @@ struct AppendParams {
   int32_t row_k_bytes, row_v_bytes;  // d_qk, d_v in bytes (multiples of 16)
 };
 
+// Decode with selective V fetching (top-k): strides in elements.
+struct TopkParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  int64_t k_sb, k_sh, k_st;
+  int64_t v_sb, v_sh, v_st;
+  const int32_t* seqlens;
+  const int32_t* block_table;
+  int32_t max_pages, page_size;
+  int32_t T, T_pad;  // bound on the lengths; row length of the score workspace (multiple of 128)
+  int32_t B, n_q, n_k, n_v, d_qk, d_v;
+  int32_t top_k, renormalize;
+  int32_t chunk;     // tokens per workgroup of the score kernel (multiple of 128)
+  float scale_log2;
+  float* scores;     // workspace [B, n_q, T_pad], base-2 domain
+  void* out;
+  float* lse_out;
+  int32_t* sel_out;  // [B, n_q, top_k + 1] or nullptr
+};
+
 // dtype: 0 = fp32, 1 = bf16 (diffqkv_dtype).  All return a hipError_t from the launch.
 hipError_t launch_decode_generic(const DecodeParams& p, int dtype, bool paged, hipStream_t s);
 bool decode_mfma_supported(const DecodeParams& p, int dtype);
@@ -70,6 +91,9 @@ hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t
 bool prefill_mfma_supported(const PrefillParams& p, int dtype);
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s);
 void set_prefill_waves(int nw);  // 4 or 8 wavefronts per workgroup (experiments)
+int topk_max_k();
+bool topk_scores_mfma_supported(const TopkParams& p, int dtype);
+hipError_t launch_topk(const TopkParams& p, int dtype, bool paged, bool mfma, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, bool paged, hipStream_t s);
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 

@@ -299,3 +299,66 @@ def test_append_paged_matches_contiguous_view():
     kc0, vc0 = brute.gather_paged(kp, bt, pos, 16), brute.gather_paged(vp, bt, pos, 16)
     for b in range(3):
         assert np.array_equal(kc[b, :, : pos[b]], kc0[b, :, : pos[b]])
+
+
+# ---- selective V-cache fetching (top-k) ---------------------------------------------------------------
+def topk_by_argsort(q, k, v, scale, top_k, renormalize):
+    """Independent numpy statement: full softmax, stable descending argsort of the previous positions."""
+    q, k, v = (brute.bf16_bits_to_f64(x) for x in (q, k, v))
+    B, n_q, _ = q.shape
+    n_k, n_v, T = k.shape[1], v.shape[1], k.shape[2]
+    out = np.zeros((B, n_q, v.shape[3]))
+    picks = []
+    for b in range(B):
+        for h in range(n_q):
+            kh, vh = h // (n_q // n_k), h // (n_q // n_v)
+            s = scale * (k[b, kh] @ q[b, h])
+            a = np.exp(s - s.max())
+            a /= a.sum()
+            order = np.argsort(-a[: T - 1], kind="stable")[:top_k]  # stable: ties keep the lower position first
+            idx = np.sort(np.concatenate([order, [T - 1]])).astype(int)
+            o = (a[idx, None] * v[b, vh, idx]).sum(axis=0)
+            out[b, h] = o / a[idx].sum() if renormalize else o
+            picks.append(idx)
+    return out, picks
+
+
+@pytest.mark.parametrize("renorm", [False, True])
+def test_topk_matches_argsort_statement(renorm):
+    q, k, v = rnd((2, 8, 16), 50), rnd((2, 2, 40, 16), 51), rnd((2, 4, 40, 8), 52)
+    for top_k in (0, 1, 5, 38, 39, 100):
+        out, _, sel = oracle.decode_topk(q, k, v, top_k, scale=0.7, renormalize=renorm)
+        ref, picks = topk_by_argsort(q, k, v, 0.7, top_k, renorm)
+        rel_close(out, ref)
+        for i, idx in enumerate(picks):
+            got = sel.reshape(-1, top_k + 1)[i]
+            assert list(got[got >= 0]) == list(idx)
+
+
+def test_topk_covering_everything_is_plain_attention():
+    q, k, v = rnd((2, 4, 8), 53), rnd((2, 1, 17, 8), 54), rnd((2, 2, 17, 8), 55)
+    full, lfull = oracle.decode(q, k, v)
+    for top_k in (16, 17, 1000):
+        for renorm in (False, True):
+            out, lse, _ = oracle.decode_topk(q, k, v, top_k, renormalize=renorm)
+            rel_close(out, full)
+            rel_close(lse, lfull)
+
+
+def test_topk_ties_go_to_the_lower_position_and_current_token_always_counts():
+    # all keys equal => all weights equal: the first top_k positions win; the last token is always in
+    q = rnd((1, 2, 8), 56)
+    k = np.ones((1, 1, 10, 8), np.float32)
+    v = rnd((1, 1, 10, 4), 57)
+    out, _, sel = oracle.decode_topk(q, k, v, 3)
+    assert list(sel[0, 0]) == [0, 1, 2, 9]
+    rel_close(out[0, 0], v[0, 0, [0, 1, 2, 9]].astype(np.float64).sum(axis=0) / 10.0)
+    # renormalised weights sum to one: constant V comes back unchanged; unnormalised: scaled by the kept mass
+    vc = np.full((1, 1, 10, 4), 2.5, np.float32)
+    rel_close(oracle.decode_topk(q, k, vc, 3, renormalize=True)[0], np.full((1, 2, 4), 2.5))
+    rel_close(oracle.decode_topk(q, k, vc, 3, renormalize=False)[0], np.full((1, 2, 4), 2.5 * 0.4))
+    # a current token with a negligible weight is still loaded
+    k2 = k.copy()
+    k2[0, 0, 9] = -50.0 * np.sign(q[0, 0])
+    _, _, sel2 = oracle.decode_topk(q, k2, v, 2)
+    assert 9 in list(sel2[0, 0]) and 9 in list(sel2[0, 1])

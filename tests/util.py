@@ -32,7 +32,8 @@ def check(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = ""):
 def check_lse(gpu: torch.Tensor, ref: np.ndarray, what: str = ""):
     g = f64(gpu)
     both_inf = np.isneginf(g) & np.isneginf(ref)
-    diff = np.where(both_inf, 0.0, np.abs(g - ref))
+    with np.errstate(invalid="ignore"):
+        diff = np.where(both_inf, 0.0, np.abs(g - ref))
     assert np.all(np.isfinite(diff)) and diff.max(initial=0.0) <= 2e-3, "%s: lse error %s" % (what, diff.max(initial=0.0))
 
 
