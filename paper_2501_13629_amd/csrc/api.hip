@@ -269,8 +269,6 @@ size_t diffqkv_decode_topk_workspace_bytes(const diffqkv_shape* shape, int32_t m
 static int run_topk(const diffqkv_shape* shape, TopkParams& p, bool paged, int32_t top_k, int32_t renormalize,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (top_k < 0 || top_k > topk_max_k()) return DIFFQKV_ERR_SHAPE;
-  const int hi = shape->n_k > shape->n_v ? shape->n_k : shape->n_v;
-  (void)hi;
   const size_t need = diffqkv_decode_topk_workspace_bytes(shape, p.T);
   if (need) {
     if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;

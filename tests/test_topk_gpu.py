@@ -105,6 +105,28 @@ def test_ties_go_to_the_lower_position():
     util.check(out, ref, "bf16")
 
 
+def test_thousands_of_ties_take_the_exact_fallback():
+    """More equal scores than the candidate buffer of the select kernel holds: the exact radix select over
+    the whole row takes over, and the lower positions still win."""
+    cfg = inputs.config("decode_4k", B=1, n_q=8, n_k=2, n_v=4, d_qk=64, d_v=64, T=6000, index=125)
+    d = inputs.make_decode(cfg)
+    d["k"][:] = d["k"][:, :, :1]
+    d["k"][:, :, 4500] = d["k"][:, :, 4500] * 0 + d["q"][:, :2]  # one row that differs: larger or smaller score
+    q, k, v = util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"])
+    out, sel = binding.diffqkv_decode_topk(q, k, v, 100, want_selection=True)
+    ref, _, ref_sel = oracle.decode_topk(inputs.as_numpy(d["q"]), inputs.as_numpy(d["k"]), inputs.as_numpy(d["v"]), 100)
+    for g, r in zip(sel.cpu().numpy().reshape(-1, 101), ref_sel.reshape(-1, 101)):
+        assert sorted(int(x) for x in g) == sorted(int(x) for x in r)
+    util.check(out, ref, "bf16")
+
+
+def test_rows_longer_than_the_register_resident_part():
+    """Above 32768 previous positions the select kernel reads the score row twice."""
+    cfg = inputs.config("decode_4k", B=1, n_q=8, n_k=2, n_v=4, d_qk=64, d_v=64, T=40000, index=126)
+    run(cfg, 100, False)
+    run(cfg, 512, True, seqlens=[32770])
+
+
 @pytest.mark.parametrize("page_size", [16, 4])
 def test_paged(page_size):
     cfg = inputs.config("paged_ragged", B=5, seqlens=[1, 17, 700, 1029, 2304], page_size=page_size, index=124)
