@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--workload", default="decode_32k",
                     choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--top-k", type=int, default=-1,
+                    help="contiguous decode workloads only: selective V-cache fetching with this top_k "
+                         "(a different, smaller byte count; not the headline metric)")
     ap.add_argument("--chunk", type=int, default=0, help="override tokens per context split (experiments)")
     return ap.parse_args()
 
@@ -58,12 +61,19 @@ def main():
     dev = torch.device("cuda:0")
     cfg = inputs.config(args.workload)
     kind = cfg["kind"]
+    topk = args.top_k
+    if topk >= 0 and kind != "decode":
+        print("bench.py: --top-k goes with the contiguous decode workloads", file=sys.stderr)
+        sys.exit(2)
     props = torch.cuda.get_device_properties(0)
 
     # ---- inputs, resident on the device ----------------------------------------------------------
     if kind == "decode":
         host = inputs.make_decode(cfg)
         kv_bytes = cfg["B"] * cfg["T"] * inputs.kv_bytes_per_token(cfg)
+        if topk >= 0:  # all of K, and per query head the selected V rows plus the current token's
+            kv_bytes = 2 * cfg["B"] * (cfg["T"] * cfg["n_k"] * cfg["d_qk"] +
+                                       cfg["n_q"] * (min(topk, cfg["T"] - 1) + 1) * cfg["d_v"])
         cache_names = ("k", "v")
     elif kind == "paged":
         host = inputs.make_paged(cfg)
@@ -86,6 +96,9 @@ def main():
         ws_bytes = binding.diffqkv_decode_workspace_bytes(cfg["B"], cfg["n_q"], cfg["n_k"], cfg["n_v"], cfg["d_qk"],
                                                           cfg["d_v"], binding.BF16,
                                                           cfg["T"] if kind == "decode" else max_T)
+        if topk >= 0:
+            ws_bytes = binding.diffqkv_decode_topk_workspace_bytes(cfg["B"], cfg["n_q"], cfg["n_k"], cfg["n_v"],
+                                                                   cfg["d_qk"], cfg["d_v"], binding.BF16, cfg["T"])
         workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         out = torch.empty((cfg["B"], cfg["n_q"], cfg["d_v"]), dtype=q.dtype, device=dev)
     else:
@@ -97,7 +110,10 @@ def main():
     def step(i):
         if kind == "decode":
             s = sets[i % n_sets]
-            binding.diffqkv_decode(q, s["k"], s["v"], out=out, workspace=workspace)
+            if topk >= 0:
+                binding.diffqkv_decode_topk(q, s["k"], s["v"], topk, out=out, workspace=workspace)
+            else:
+                binding.diffqkv_decode(q, s["k"], s["v"], out=out, workspace=workspace)
         elif kind == "paged":
             s = sets[i % n_sets]
             binding.diffqkv_decode_paged(q, s["k_pool"], s["v_pool"], bt, sl, out=out, workspace=workspace)
@@ -130,7 +146,7 @@ def main():
         ev2[i].record()
     binding.diffqkv_set_split_event(None)
     torch.cuda.synchronize()
-    if kind != "prefill":
+    if kind != "prefill" and topk < 0:
         main_us = sorted(ev0[i].elapsed_time(ev1[i]) * 1e3 for i in range(n_ev))
         tail_us = sorted(ev1[i].elapsed_time(ev2[i]) * 1e3 for i in range(n_ev))
     else:
@@ -160,10 +176,13 @@ def main():
     if kind != "prefill":
         value = kv_bytes / (ms_per_step * 1e-3) / 1e9
         metric, unit = "decode-attention achieved HBM GB/s", "GB/s"
+        if topk >= 0:
+            metric = "decode-attention with top-%d V fetching, algorithmic GB/s" % topk
         achieved = kv_bytes / (avg_main_us * 1e-6) / 1e9
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "kernel": "decode_mfma_kernel (split)", "kernel_avg_us": round(avg_main_us, 2),
+                "kernel": "decode_mfma_kernel (split)" if topk < 0 else "topk_scores + topk_select (both)",
+                "kernel_avg_us": round(avg_main_us, 2),
                 "kernel_min_us": round(main_us[0], 2), "combine_avg_us": round(sum(tail_us) / len(tail_us), 2),
                 "algorithmic_bytes_per_launch": kv_bytes,
                 "stream_read_ceiling_GBps": None if ceiling is None else round(ceiling, 1)}
@@ -178,18 +197,18 @@ def main():
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc (see profiles/)
         with open(traffic_file) as f:
-            roof["traffic"] = json.load(f).get(args.workload)
+            roof["traffic"] = json.load(f).get(args.workload if topk < 0 else "%s_topk%d" % (args.workload, topk))
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, host, kind, kv_bytes)
+        cpu = cpu_baseline(cfg, host, kind, kv_bytes, topk)
 
     line = {
         "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4) if kind != "prefill" else None,
-        "config": {"workload": args.workload, **{k: v for k, v in cfg.items()
+        "config": {"workload": args.workload if topk < 0 else "%s, top_k=%d" % (args.workload, topk), **{k: v for k, v in cfg.items()
                                                  if k in ("B", "n_q", "n_k", "n_v", "d_qk", "d_v", "T", "S", "page_size")},
                    "kv_bytes_per_step": kv_bytes, "cache_sets_in_rotation": n_sets,
                    "device": props.name, "compute_units": props.multi_processor_count},
@@ -198,7 +217,7 @@ def main():
     print(json.dumps(line))
 
 
-def cpu_baseline(cfg, host, kind, kv_bytes):
+def cpu_baseline(cfg, host, kind, kv_bytes, topk=-1):
     """The float64 oracle as it stands, on the host cores, over a bounded sample of the workload."""
     import numpy as np
 
@@ -208,7 +227,10 @@ def cpu_baseline(cfg, host, kind, kv_bytes):
     a = inputs.as_numpy
     threads = oracle.num_threads()
     if kind == "decode":
-        fn = lambda: oracle.decode(a(host["q"]), a(host["k"]), a(host["v"]))
+        if topk >= 0:
+            fn = lambda: oracle.decode_topk(a(host["q"]), a(host["k"]), a(host["v"]), topk)
+        else:
+            fn = lambda: oracle.decode(a(host["q"]), a(host["k"]), a(host["v"]))
         work, unit, sample = kv_bytes / 1e9, "GB/s", "the full workload, one evaluation"
     elif kind == "paged":
         n = 16  # sequences

@@ -151,6 +151,11 @@ def diffqkv_decode_workspace_bytes(B, n_q, n_k, n_v, d_qk, d_v, dtype, max_T) ->
     return int(load_library().diffqkv_decode_workspace_bytes(ctypes.byref(s), int(max_T)))
 
 
+def diffqkv_decode_topk_workspace_bytes(B, n_q, n_k, n_v, d_qk, d_v, dtype, max_T) -> int:
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dtype, None)
+    return int(load_library().diffqkv_decode_topk_workspace_bytes(ctypes.byref(s), int(max_T)))
+
+
 def _workspace(nbytes: int, like: torch.Tensor, workspace):
     if workspace is not None:
         return workspace

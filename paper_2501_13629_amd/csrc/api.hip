@@ -283,7 +283,9 @@ static int run_topk(const diffqkv_shape* shape, TopkParams& p, bool paged, int32
   p.d_v = shape->d_v;
   p.top_k = top_k;
   p.renormalize = renormalize ? 1 : 0;
-  p.chunk = 1024;
+  p.chunk = g_tuning.decode_chunk_tokens > 0
+                ? (g_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum
+                : 512;
   p.scale_log2 = scale_log2(shape);
   p.scores = (float*)workspace;
   if (shape->B == 0) return DIFFQKV_OK;
