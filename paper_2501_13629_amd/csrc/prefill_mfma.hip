@@ -37,6 +37,16 @@ constexpr int kBN = 64;  // tokens per K/V tile
 constexpr int kXcds = 8;
 constexpr float kSlack = 8.f;  // log2 units a row maximum may exceed the softmax reference
 
+// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N - 1, so that every register-array
+// index in the body is a constant for the front end already.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 x = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
@@ -68,14 +78,19 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
-// NW wavefronts of 32 query rows each per workgroup (4 or 8).  With 8 the K/V tile is staged once
-// for 256 query rows, and half of the wavefronts stage K while the other half transpose V.
-template <int DQK, int DV, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams p, int n_qtiles, int xcd_aware) {
+// NW wavefronts (4 or 8) of QB x 32 query rows each per workgroup.  With 8 wavefronts the K/V tile is
+// staged once for 256 query rows, and half of the wavefronts stage K while the other half transpose
+// V.  With QB = 2 (4 wavefronts, one per SIMD, the whole register file each: accumulators in the
+// accumulation registers) every K and V^T fragment read from LDS feeds two matrix instructions, which
+// halves the LDS traffic per flop.
+template <int DQK, int DV, int NW, int QB>
+__global__ __launch_bounds__(NW * 64, QB == 2 ? 1 : 2) void prefill_mfma_kernel(PrefillParams p, int n_qtiles,
+                                                                               int xcd_aware) {
   constexpr int KS = DQK / 16;  // k-steps of the score product (16 channels each)
   constexpr int CB = DV / 32;   // 32-channel blocks of the output
   constexpr int kThreads = NW * 64;
-  constexpr int kBM = NW * 32;
+  constexpr int kWaveRows = 32 * QB;
+  constexpr int kBM = NW * kWaveRows;
   __shared__ Smem<DQK, DV> sm;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -106,7 +121,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   const int kh = (int)(((int64_t)h * p.n_k) / p.n_q), vh = (int)(((int64_t)h * p.n_v) / p.n_q);
   const int off = p.S_k - p.S_q;        // query i sees keys j <= i + off when causal
   const int q0 = qtile * kBM;           // first query row of the workgroup
-  const int r0 = q0 + wave * 32;        // first query row of this wavefront
+  const int r0 = q0 + wave * kWaveRows;  // first query row of this wavefront
 
   const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h) * p.S_q * DQK;
   const rsrc_t k_rsrc = make_rsrc((const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * DQK, p.S_k * DQK * 2);
@@ -117,20 +132,21 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   if (p.causal) {
     const int lastq = (q0 + kBM < p.S_q ? q0 + kBM : p.S_q) - 1;
     wg_limit = lastq + off + 1;
-    int lastw = r0 + 31;
+    int lastw = r0 + kWaveRows - 1;
     lastw = lastw < p.S_q ? lastw : p.S_q - 1;
     wave_limit = lastw + off + 1;
   }
   const int n_tiles = (wg_limit + kBN - 1) / kBN;
 
   // ---- Q^T as the B operand: lane (half, n) holds channels 16 ks + 8 half .. + 7 of its row ------
-  bf16x8 qf[KS];
-  {
-    int row = r0 + n;
+  bf16x8 qf[QB][KS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    int row = r0 + 32 * qb + n;
     row = row < p.S_q ? row : p.S_q - 1;
     const uint16_t* qrow = qbase + (int64_t)row * DQK + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + ks * 16));
   }
 
   // ---- global -> register -> LDS staging of one K/V tile ---------------------------------------------
@@ -192,12 +208,17 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
     }
   };
 
-  f32x16 acc[CB];
+  f32x16 acc[QB][CB];
+  float m_run[QB], l_run[QB];
 #pragma unroll
-  for (int cb = 0; cb < CB; ++cb)
+  for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[qb][cb][r] = 0.f;
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+  }
 
   load_tile(0);
   store_tile(0);
@@ -205,7 +226,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   // are still in flight when the loop is entered, makes every iteration wait on the vector-memory
   // counter -- and with it on the next tile's staging loads -- before each matrix instruction.
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]));
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[qb][ks]));
   __syncthreads();
 
   // One tile step.  MASKED is a compile-time flag: tiles strictly below the diagonal of this
@@ -225,12 +248,29 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
       // and the two blocks are written interleaved -- the score product of block 1 between the
       // softmax pieces of block 0, the softmax of block 1 between the output products of block 0 --
       // so that the vector ALU (exponentials) and the matrix cores work at the same time.
-      const int row_limit = p.causal ? r0 + n + off : p.S_k - 1;  // last visible token of this row
-      f32x16 s[2];
-      uint32_t pw[2][8];
-      auto score_step = [&](int blk, int ks) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sm.k[buf][32 * blk + n][16 * ks + 8 * half]);
-        s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[blk], 0, 0, 0);
+      int row_limit[QB];  // last visible token of this lane's row in each row block
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) row_limit[qb] = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
+      f32x16 s[QB][2];
+      uint32_t pw[QB][2][8];
+      // The operand fragments of the tile, in the order the matrix instructions consume them:
+      //   K rows of block 0 (KS k-steps), K rows of block 1, V^T of block 0 (2 token halves x CB
+      //   channel blocks), V^T of block 1.
+      // They pass through a ring of kRing register slots: the LDS read of fragment f + kRing is issued
+      // as soon as fragment f has been consumed, so LDS latency stays off the matrix pipeline.
+      constexpr int kRing = 8;
+      constexpr int kFrags = 2 * KS + 4 * CB;
+      u32x4 fr[kRing];
+      auto fetch = [&](auto fc) {
+        constexpr int f = decltype(fc)::value;
+        if constexpr (f < 2 * KS) {
+          constexpr int blk = f / KS, ks = f % KS;
+          fr[f % kRing] = *(const u32x4*)&sm.k[buf][32 * blk + n][16 * ks + 8 * half];
+        } else {
+          constexpr int j = f - 2 * KS, kq = j / CB, cb = j % CB;  // kq: 16-token step of the tile
+          const int ch = 32 * cb + n;
+          fr[f % kRing] = *(const u32x4*)&sm.vt[buf][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3];
+        }
       };
       // softmax reference for one block; register r: token t0 + 32 blk + 8 (r/4) + 4 half + r%4.
       // Scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - m_ref).  The
@@ -238,75 +278,95 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
       // running maximum: it is raised (and the accumulators rescaled) only when some row's maximum
       // exceeds it by more than kSlack, so most blocks skip the rescale.  Weights are then at most
       // 2^kSlack, well inside bf16 / fp32 range; the final division by the row sum removes it.
-      auto reference = [&](int blk) {
+      // Each lane first tests the 16 tokens it holds; the exchange with the lane that holds the
+      // row's other 16 happens only when some lane of the wavefront needs a higher reference.
+      auto reference = [&](int qb, int blk) {
         float m_blk = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float v = s[blk][r];
+          float v = s[qb][blk][r];
           if (MASKED) {
             const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
-            v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
-            s[blk][r] = v;
+            v = (tok <= row_limit[qb] && tok < p.S_k) ? v : -INFINITY;
+            s[qb][blk][r] = v;
           }
           m_blk = fmaxf(m_blk, v);
         }
-        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
-        const float m_cand = m_blk * p.scale_log2;
-        const bool raise = m_cand > m_run + kSlack;
         float fac = 1.f;
-        if (__builtin_amdgcn_ballot_w64(raise)) {
-          const float m_new = raise ? m_cand : m_run;
-          fac = __builtin_amdgcn_exp2f(m_run - m_new);  // first block: exp2(-inf) = 0
-          m_run = m_new;
-          l_run *= fac;
+        if (__builtin_amdgcn_ballot_w64(m_blk * p.scale_log2 > m_run[qb] + kSlack)) {
+          m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
+          const float m_cand = m_blk * p.scale_log2;
+          const float m_new = (m_cand > m_run[qb] + kSlack) ? m_cand : m_run[qb];
+          fac = __builtin_amdgcn_exp2f(m_run[qb] - m_new);  // first block: exp2(-inf) = 0
+          m_run[qb] = m_new;
+          l_run[qb] *= fac;
         }
         return fac;  // the caller rescales the accumulators once they hold everything older
       };
-      auto rescale = [&](float fac) {
+      auto rescale = [&](int qb, float fac) {
         if (__builtin_amdgcn_ballot_w64(fac != 1.f)) {
 #pragma unroll
-          for (int cb = 0; cb < CB; ++cb) acc[cb] *= fac;
+          for (int cb = 0; cb < CB; ++cb) acc[qb][cb] *= fac;
         }
       };
-      auto weights_step = [&](int blk, int i) {  // two of the block's 16 weights
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i], p.scale_log2, -m_run));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[blk][2 * i + 1], p.scale_log2, -m_run));
-        pw[blk][i] = pack_bf16x2(p0, p1);
-        l_run += p0 + p1;
+      auto weights_step = [&](int blk, int w) {  // w in [0, 8 QB): two of a row block's 16 weights
+        const int qb = w / 8, i = w % 8;
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i], p.scale_log2, -m_run[qb]));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i + 1], p.scale_log2, -m_run[qb]));
+        pw[qb][blk][i] = pack_bf16x2(p0, p1);
+        l_run[qb] += p0 + p1;
       };
-      auto output_step = [&](int blk, int kh2, int cb) {  // k-step kh2 (16 tokens) of block blk
-        const int kq = 2 * blk + kh2, sh = kh2 * 4;
-        const u32x4 pb = {pw[blk][sh], pw[blk][sh + 1], pw[blk][sh + 2], pw[blk][sh + 3]};
-        const int ch = 32 * cb + n;
-        const bf16x8 a = __builtin_bit_cast(
-            bf16x8, *(const u32x4*)&sm.vt[buf][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3]);
-        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb), acc[cb], 0, 0, 0);
-      };
+      constexpr int W = 8 * QB;  // weight pairs per block
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+      for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[blk][r] = 0.f;
+        for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) score_step(0, ks);
-      rescale(reference(0));
+          for (int r = 0; r < 16; ++r) s[qb][blk][r] = 0.f;
+      static_for<0, kRing>(fetch);
+      __builtin_amdgcn_sched_barrier(0);  // keep the first reads together, ahead of the matrix instructions
+      float fac1[QB];
+      static_for<0, kFrags>([&](auto fc) {
+        constexpr int f = decltype(fc)::value;
+        const bf16x8 a = __builtin_bit_cast(bf16x8, fr[f % kRing]);
+        if constexpr (f < 2 * KS) {  // score product: block f / KS, k-step f % KS
+          constexpr int blk = f / KS, ks = f % KS;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        score_step(1, ks);
-        if (ks * 8 / KS != (ks + 1) * 8 / KS || KS == 8) {
+          for (int qb = 0; qb < QB; ++qb)
+            s[qb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][blk], 0, 0, 0);
+        } else {           // output product: block blk, 16-token half kh2, channel block cb
+          constexpr int j = f - 2 * KS, blk = j / (2 * CB), kh2 = (j / CB) % 2, cb = j % CB, sh = kh2 * 4;
 #pragma unroll
-          for (int i = ks * 8 / KS; i < (ks + 1) * 8 / KS; ++i) weights_step(0, i);
+          for (int qb = 0; qb < QB; ++qb) {
+            const u32x4 pb = {pw[qb][blk][sh], pw[qb][blk][sh + 1], pw[qb][blk][sh + 2], pw[qb][blk][sh + 3]};
+            acc[qb][cb] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb), acc[qb][cb], 0, 0, 0);
+          }
         }
-      }
-      const float fac1 = reference(1);
+        if constexpr (f + kRing < kFrags) fetch(std::integral_constant<int, f + kRing>{});
+        // the softmax pieces, placed between the matrix instructions they can overlap with
+        if constexpr (f == KS - 1) {
 #pragma unroll
-      for (int j = 0; j < 2 * CB; ++j) {
-        output_step(0, j / CB, j % CB);
+          for (int qb = 0; qb < QB; ++qb) rescale(qb, reference(qb, 0));
+        } else if constexpr (f >= KS && f < 2 * KS) {  // weights of block 0 under the score product of block 1
+          constexpr int i = f - KS;
 #pragma unroll
-        for (int i = j * 8 / (2 * CB); i < (j + 1) * 8 / (2 * CB); ++i) weights_step(1, i);
-      }
-      rescale(fac1);  // block 0's weights were taken against the older reference: apply it after them
+          for (int w = i * W / KS; w < (i + 1) * W / KS; ++w) weights_step(0, w);
+          if constexpr (f == 2 * KS - 1) {
 #pragma unroll
-      for (int j = 0; j < 2 * CB; ++j) output_step(1, j / CB, j % CB);
+            for (int qb = 0; qb < QB; ++qb) fac1[qb] = reference(qb, 1);
+          }
+        } else if constexpr (f >= 2 * KS && f < 2 * KS + 2 * CB) {  // weights of block 1 under block 0's output product
+          constexpr int i = f - 2 * KS;
+#pragma unroll
+          for (int w = i * W / (2 * CB); w < (i + 1) * W / (2 * CB); ++w) weights_step(1, w);
+          // block 0's weights were taken against the older reference: apply the new one after them
+          if constexpr (f == 2 * KS + 2 * CB - 1) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) rescale(qb, fac1[qb]);
+          }
+        }
+      });
     }
     if (more) store_tile(buf ^ 1);
     __syncthreads();
@@ -322,24 +382,27 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_mfma_kernel(PrefillParams 
   for (; it < n_plain; ++it) tile_step(it, std::false_type{});
   for (; it < n_tiles; ++it) tile_step(it, std::true_type{});
 
-  // ---- write this wavefront's rows: lane (half, n), acc[cb][r] = row n, channel
+  // ---- write this wavefront's rows: lane (half, n), acc[qb][cb][r] = row 32 qb + n, channel
   //      32 cb + 8 (r/4) + 4 half + r%4.  Both halves hold the full row sum after the exchange.
-  const int my_row = r0 + n;
-  const float l = l_run + __shfl_xor(l_run, 32, 64);
-  if (my_row < p.S_q) {
-    const float inv = 1.f / l;
-    uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * DV;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+  for (int qb = 0; qb < QB; ++qb) {
+    const int my_row = r0 + 32 * qb + n;
+    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+    if (my_row < p.S_q) {
+      const float inv = 1.f / l;
+      uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * DV;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 w;
-        w[0] = pack_bf16x2(acc[cb][4 * q4] * inv, acc[cb][4 * q4 + 1] * inv);
-        w[1] = pack_bf16x2(acc[cb][4 * q4 + 2] * inv, acc[cb][4 * q4 + 3] * inv);
-        *(u32x2*)(orow + 32 * cb + 8 * q4 + 4 * half) = w;
-      }
-    if (half == 0 && p.lse_out)
-      p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run + log2f(l)) * kLn2;
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
+          w[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
+          *(u32x2*)(orow + 32 * cb + 8 * q4 + 4 * half) = w;
+        }
+      if (half == 0 && p.lse_out)
+        p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
+    }
   }
 }
 
@@ -354,27 +417,32 @@ bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
 }
 
 namespace {
-int g_prefill_waves = 8;
-template <int DQK, int DV, int NW>
+int g_prefill_waves = 8;  // 8: 8 wavefronts x 32 rows; 4: 4 x 32; 2: 4 wavefronts x 64 rows
+template <int DQK, int DV, int NW, int QB>
 hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
-  constexpr int kBM = NW * 32;
+  constexpr int kBM = NW * 32 * QB;
   const int n_qtiles = (p.S_q + kBM - 1) / kBM;
   const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
-  prefill_mfma_kernel<DQK, DV, NW><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
+  prefill_mfma_kernel<DQK, DV, NW, QB><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
   return hipGetLastError();
+}
+template <int DQK, int DV>
+hipError_t launch_variant(const PrefillParams& p, hipStream_t s) {
+  if (g_prefill_waves == 2) return launch_nw<DQK, DV, 4, 2>(p, s);
+  if (g_prefill_waves == 4) return launch_nw<DQK, DV, 4, 1>(p, s);
+  return launch_nw<DQK, DV, 8, 1>(p, s);
 }
 }  // namespace
 
-void set_prefill_waves(int nw) { g_prefill_waves = (nw == 4) ? 4 : 8; }
+void set_prefill_waves(int nw) { g_prefill_waves = (nw == 4 || nw == 2) ? nw : 8; }
 
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
-  const bool eight = g_prefill_waves == 8;
-  if (p.d_qk == 128) return eight ? launch_nw<128, 128, 8>(p, s) : launch_nw<128, 128, 4>(p, s);
-  if (p.d_v == 128) return eight ? launch_nw<64, 128, 8>(p, s) : launch_nw<64, 128, 4>(p, s);
-  return eight ? launch_nw<64, 64, 8>(p, s) : launch_nw<64, 64, 4>(p, s);
+  if (p.d_qk == 128) return launch_variant<128, 128>(p, s);
+  if (p.d_v == 128) return launch_variant<64, 128>(p, s);
+  return launch_variant<64, 64>(p, s);
 }
 
 }  // namespace diffqkv

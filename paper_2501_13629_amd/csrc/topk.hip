@@ -12,10 +12,11 @@
 //            in the full decode kernel (K rows straight from HBM in operand layout, non-temporal),
 //            scaled scores (base-2 domain) written as fp32 to the workspace, -inf beyond T_b.
 //            A portable vector-ALU variant serves fp32 and the shapes the MFMA variant leaves out.
-//   select   one workgroup per (sequence, query head): log-sum-exp of the row, an exact radix select
-//            of the top_k-th largest score among the previous positions (4 rounds of 8 bits over a
-//            monotone integer image of the floats; LDS histograms), in-order compaction of the
-//            winners (ties in position order), then the weighted sum of the gathered V rows.
+//   select   one 1024-thread workgroup per (sequence, query head): maximum and a coarse histogram of
+//            an order-preserving integer image of the scores locate the bin of the top_k-th largest
+//            among the previous positions; the positions at or above it become candidates in LDS,
+//            where three more radix rounds settle the threshold exactly; ties go by position; the
+//            winners are put into position order, then their V rows are gathered and summed.
 //            Integer counting only: the selection does not depend on thread scheduling.
 #include "kernels.h"
 
