@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--top-k", type=int, default=-1,
                     help="contiguous decode workloads only: selective V-cache fetching with this top_k "
                          "(a different, smaller byte count; not the headline metric)")
+    ap.add_argument("--prefill-waves", type=int, default=0, help="prefill kernel variant (experiments)")
     ap.add_argument("--chunk", type=int, default=0, help="override tokens per context split (experiments)")
     return ap.parse_args()
 
@@ -57,7 +58,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     binding.load_library()  # fail loudly if the HIP library is not built
-    binding.diffqkv_set_tuning(decode_chunk_tokens=args.chunk)
+    binding.diffqkv_set_tuning(decode_chunk_tokens=args.chunk, prefill_waves=args.prefill_waves)
     dev = torch.device("cuda:0")
     cfg = inputs.config(args.workload)
     kind = cfg["kind"]

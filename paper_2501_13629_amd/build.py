@@ -17,7 +17,7 @@ INCLUDE = PKG.parent / "include"
 LIB = PKG / "libdiffqkv.so"
 OBJ = PKG / "_build"
 
-SOURCES = ["api.hip", "decode_generic.hip", "decode_mfma.hip", "prefill_generic.hip", "prefill_mfma.hip", "probe.hip", "append.hip", "topk.hip"]
+SOURCES = ["api.hip", "decode_generic.hip", "decode_mfma.hip", "prefill_generic.hip", "prefill_mfma.hip", "prefill_mfma64.hip", "probe.hip", "append.hip", "topk.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -38,7 +38,7 @@ def stale() -> bool:
     if not LIB.exists():
         return True
     t = LIB.stat().st_mtime
-    deps = [CSRC / s for s in SOURCES] + [CSRC / "kernels.h", INCLUDE / "diffqkv.h", Path(__file__)]
+    deps = [CSRC / s for s in SOURCES] + [CSRC / "kernels.h", CSRC / "prefill_tile.h", INCLUDE / "diffqkv.h", Path(__file__)]
     return any(d.stat().st_mtime > t for d in deps)
 
 

@@ -90,6 +90,7 @@ hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t s);
 bool prefill_mfma_supported(const PrefillParams& p, int dtype);
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s);
+hipError_t launch_prefill_mfma64(const PrefillParams& p, hipStream_t s);  // 64 query rows per wavefront
 void set_prefill_waves(int nw);  // 4 or 8 wavefronts per workgroup (experiments)
 int topk_max_k();
 bool topk_scores_mfma_supported(const TopkParams& p, int dtype);

@@ -18,65 +18,13 @@
 //                  token order that the score layout produces.
 // Workgroups are ordered so that the query heads sharing a K head run side by side on one XCD
 // (its L2 then serves their common K/V tiles), heaviest query tiles first.
-#include <type_traits>
-
-#include "kernels.h"
+#include "prefill_tile.h"
 
 namespace diffqkv {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-constexpr int kBN = 64;  // tokens per K/V tile
-constexpr int kXcds = 8;
-constexpr float kSlack = 8.f;  // log2 units a row maximum may exceed the softmax reference
-
-// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N - 1, so that every register-array
-// index in the body is a constant for the front end already.
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  f32x2 x = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-}
-
-// Transposed V tile in LDS: row = channel, 64 token positions (128 B, no padding).
-// Position of token t (0..63): within each group of 16 tokens the quads are stored in the order
-// 0, 2, 1, 3, so that the 8 tokens a lane needs for one k-step of the PV product (quads u and
-// u + 2) form one 16-byte granule.  The granule index is XOR-swizzled with the channel so that
-// both the 16-byte operand reads (32 consecutive channels) and the 8-byte transposed writes
-// (channels 8 apart) spread over the banks (measured: no bank conflicts).
-__device__ __forceinline__ int vt_pos(int t) {
-  const int u = (t >> 2) & 3;
-  return (t & ~15) + 8 * (u & 1) + 4 * (u >> 1) + (t & 3);
-}
-__device__ __forceinline__ int vt_swizzle(int ch) { return (ch ^ (ch >> 3)) & 7; }
-
-template <int DQK, int DV>
-struct Smem {
-  static constexpr int kKPitch = DQK + 8;  // bf16 elements per K row (16 B of padding)
-  uint16_t k[2][kBN][kKPitch];
-  uint16_t vt[2][DV][kBN];
-};
-
-// Raw buffer resource over `bytes` bytes: loads take a scalar byte offset (the tile start) on top
-// of a loop-invariant per-lane offset, and rows past the end of the tensor read as zero.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
+using namespace prefill_tile;
 
 // NW wavefronts (4 or 8) of QB x 32 query rows each per workgroup.  With 8 wavefronts the K/V tile is
 // staged once for 256 query rows, and half of the wavefronts stage K while the other half transpose
@@ -98,26 +46,8 @@ __global__ __launch_bounds__(NW * 64, QB == 2 ? 1 : 2) void prefill_mfma_kernel(
   const int half = lane >> 5, n = lane & 31;
 
   // ---- which (sequence, query head, query tile) ---------------------------------------------------
-  const int g_k = p.n_q / p.n_k;
   int b, h, qtile;
-  {
-    const int x = blockIdx.x;
-    if (xcd_aware) {
-      // groups (sequence, K head) are dealt round-robin to the XCDs; inside an XCD's queue the query
-      // heads of a group are adjacent, groups next, query tiles from the last (heaviest) down
-      const int groups_per_xcd = p.B * p.n_k / kXcds;
-      const int c = x % kXcds, j = x / kXcds;
-      const int hq = j % g_k, t = j / g_k;
-      const int group = (t % groups_per_xcd) * kXcds + c;
-      qtile = n_qtiles - 1 - t / groups_per_xcd;
-      b = group / p.n_k;
-      h = (group % p.n_k) * g_k + hq;
-    } else {
-      h = x % p.n_q;
-      b = (x / p.n_q) % p.B;
-      qtile = n_qtiles - 1 - x / (p.n_q * p.B);
-    }
-  }
+  locate_block(p, blockIdx.x, n_qtiles, xcd_aware, b, h, qtile);
   const int kh = (int)(((int64_t)h * p.n_k) / p.n_q), vh = (int)(((int64_t)h * p.n_v) / p.n_q);
   const int off = p.S_k - p.S_q;        // query i sees keys j <= i + off when causal
   const int q0 = qtile * kBM;           // first query row of the workgroup
@@ -417,7 +347,7 @@ bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
 }
 
 namespace {
-int g_prefill_waves = 8;  // 8: 8 wavefronts x 32 rows; 4: 4 x 32; 2: 4 wavefronts x 64 rows
+int g_prefill_waves = 8;  // 8: 8 wavefronts x 32 rows; 4: 4 x 32; 2: the 64-rows-per-wavefront kernel
 template <int DQK, int DV, int NW, int QB>
 hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
   constexpr int kBM = NW * 32 * QB;
@@ -430,7 +360,7 @@ hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
 }
 template <int DQK, int DV>
 hipError_t launch_variant(const PrefillParams& p, hipStream_t s) {
-  if (g_prefill_waves == 2) return launch_nw<DQK, DV, 4, 2>(p, s);
+  if (g_prefill_waves == 2) return launch_prefill_mfma64(p, s);
   if (g_prefill_waves == 4) return launch_nw<DQK, DV, 4, 1>(p, s);
   return launch_nw<DQK, DV, 8, 1>(p, s);
 }

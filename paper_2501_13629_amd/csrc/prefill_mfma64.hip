@@ -1,0 +1,426 @@
+// Causal prefill for bf16 on gfx950 matrix cores, 64 query rows per wavefront.
+//
+// Same attention and same tile layout in LDS as prefill_mfma.hip (section 2, "Formulation of DiffQKV
+// Attention"; head map of the "idx" rule, section 3.2), organised for the other end of the register
+// trade-off: one workgroup = 4 wavefronts = 256 query rows, one wavefront per SIMD with the whole
+// register file.  Each wavefront owns two blocks of 32 rows, so every K or V^T fragment read from LDS
+// feeds two matrix instructions -- half the LDS traffic per flop -- and the 64 x d_v output
+// accumulators live in the accumulation registers, which the matrix instructions address directly.
+//
+// With a single wavefront per SIMD nothing but the instruction stream itself overlaps the vector
+// ALU (exponentials) with the matrix cores, so the loop is software-pipelined over 32-token blocks.
+// For tile t (blocks 0 and 1) a step runs four phases of 16 matrix instructions each, every one
+// interleaved with one row block's worth of softmax weights:
+//     1  S0(t)   = K0 Q^T          ||  weights of block 1 of tile t-1, row block 1
+//        reference(block 0)
+//     2  O      += V1(t-1)^T P1    ||  weights of block 0, row block 0
+//        (accumulator rescale if the reference rose)
+//     3  S1(t)   = K1 Q^T          ||  weights of block 0, row block 1
+//        reference(block 1)
+//     4  O      += V0(t)^T P0      ||  weights of block 1, row block 0
+//        (rescale)
+// so the output product of a tile's second block runs one step late, from the LDS buffer the next
+// step has not yet overwritten.  The matrix instructions are written as inline assembly to pin the
+// score tiles to vector registers and the accumulators to accumulation registers; the wait states
+// the hardware needs between a matrix instruction and a vector-ALU access to its result, which the
+// compiler cannot insert for inline assembly, are spelled out (settle_*).
+#include "prefill_tile.h"
+
+namespace diffqkv {
+
+namespace {
+
+using namespace prefill_tile;
+
+constexpr float kMinRef = -1.0e30f;  // initial softmax reference: finite, so that exp2(-inf - ref) = 0
+
+// d = a b^T (+ d): 32x32x16 bf16, results in vector registers (scores) or accumulation registers (output)
+// (score product: the B operand, Q^T, is read from accumulation registers too -- Q stays there for the
+// whole kernel and leaves the vector registers to the softmax)
+__device__ __forceinline__ void mfma_first_v(f32x16& d, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_v(f32x16& d, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_a(f32x16& d, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+}
+// Wait states between the last matrix instruction writing these registers and the first vector-ALU
+// instruction touching them (and the other way round).  16 + 4 covers the 8-pass instruction.
+__device__ __forceinline__ void settle_v(f32x16& x, f32x16& y) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(x), "+v"(y));
+}
+template <int CB>
+__device__ __forceinline__ void settle_a(f32x16 (&acc)[2][CB]) {
+  if constexpr (CB == 4) {
+    asm volatile("s_nop 15\n\ts_nop 3"
+                 : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]),
+                   "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]));
+  } else {
+    asm volatile("s_nop 15\n\ts_nop 3" : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[1][0]), "+a"(acc[1][1]));
+  }
+}
+
+// K double-buffered, V^T triple-buffered: the output product of a tile's second block runs during the
+// next step, while the staging stores of the step after that are already being written.
+template <int DQK, int DV>
+struct Smem64 {
+  static constexpr int kKPitch = DQK + 8;  // bf16 elements per K row (16 B of padding)
+  uint16_t k[2][kBN][kKPitch];
+  uint16_t vt[3][DV][kBN];
+};
+
+template <int DQK, int DV>
+__global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p, int n_qtiles, int xcd_aware) {
+  constexpr int KS = DQK / 16;  // k-steps of the score product (16 channels each)
+  constexpr int CB = DV / 32;   // 32-channel blocks of the output
+  constexpr int kThreads = 256;
+  constexpr int kBM = 256;
+  __shared__ Smem64<DQK, DV> sm;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int half = lane >> 5, n = lane & 31;
+
+  int b, h, qtile;
+  locate_block(p, blockIdx.x, n_qtiles, xcd_aware, b, h, qtile);
+  const int kh = (int)(((int64_t)h * p.n_k) / p.n_q), vh = (int)(((int64_t)h * p.n_v) / p.n_q);
+  const int off = p.S_k - p.S_q;   // query i sees keys j <= i + off when causal
+  const int q0 = qtile * kBM;      // first query row of the workgroup
+  const int r0 = q0 + wave * 64;   // first query row of this wavefront
+
+  const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h) * p.S_q * DQK;
+  const rsrc_t k_rsrc = make_rsrc((const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * DQK, p.S_k * DQK * 2);
+  const rsrc_t v_rsrc = make_rsrc((const uint16_t*)p.v + ((int64_t)b * p.n_v + vh) * p.S_k * DV, p.S_k * DV * 2);
+
+  // tokens this workgroup / this wavefront can see
+  int wg_limit = p.S_k, wave_limit = p.S_k;
+  if (p.causal) {
+    const int lastq = (q0 + kBM < p.S_q ? q0 + kBM : p.S_q) - 1;
+    wg_limit = lastq + off + 1;
+    int lastw = r0 + 63;
+    lastw = lastw < p.S_q ? lastw : p.S_q - 1;
+    wave_limit = lastw + off + 1;  // (<= 0 for a wavefront whose rows are all past S_q: it only stages)
+  }
+  const int n_tiles = (wg_limit + kBN - 1) / kBN;
+
+  // ---- Q^T as the B operand: lane (half, n) holds channels 16 ks + 8 half .. + 7 of its two rows ----
+  u32x4 qf[2][KS];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    int row = r0 + 32 * qb + n;
+    row = row < p.S_q ? row : p.S_q - 1;
+    const uint16_t* qrow = qbase + (int64_t)row * DQK + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const u32x4*)(qrow + ks * 16);
+  }
+
+  // ---- global -> register -> LDS staging of one K/V tile (every thread takes part in both) ----------
+  // K tile = 64 rows x d_qk channels = one contiguous run of 16-byte pieces; thread t takes pieces
+  // t, t + 256, ...  V tile: 16 token quads x d_v/8 channel chunks, one (quad, chunk) per thread: it
+  // loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to high:
+  // chunk[2:0], quad-order bit 1, chunk[3] (d_v = 128 only), quad-order bit 0, 16-token group -- lanes
+  // that write the same channel rows in one instruction differ in the half-granule they write.
+  constexpr int KLD = kBN * (DQK / 8) / kThreads;
+  constexpr int kChunkBits = (DV == 128) ? 4 : 3;
+  constexpr int kVItems = 16 * (DV / 8);
+  const bool v_role = wave < kVItems / 64;  // whole wavefronts
+  const int v_c8 = (tid & 7) | ((kChunkBits == 4) ? ((tid >> 1) & 8) : 0);
+  const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
+  const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
+  const int v_voff = (4 * v_tq) * (DV * 2) + v_c8 * 16;
+  u32x4 kst[KLD], vst[4];
+  auto load_tile = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < KLD; ++i)
+      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kThreads + tid) * 16, t0 * (DQK * 2), 0);
+    if (v_role) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+        vst[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2), t0 * (DV * 2), 0);
+    }
+  };
+  auto store_tile = [&](int buf, int vbuf) {
+#pragma unroll
+    for (int i = 0; i < KLD; ++i) {
+      const int piece = i * kThreads + tid;
+      *(u32x4*)&sm.k[buf][piece / (DQK / 8)][(piece % (DQK / 8)) * 8] = kst[i];
+    }
+    if (v_role) {
+      const int pos = vt_pos(4 * v_tq);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // channel e of the chunk: word e/2, low or high half, from the 4 tokens
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 w;
+        w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
+        w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
+        const int ch = v_c8 * 8 + e;
+        *(u32x2*)&sm.vt[vbuf][ch][(((pos >> 3) ^ vt_swizzle(ch)) << 3) + (pos & 7)] = w;
+      }
+    }
+  };
+
+  // ---- state ----------------------------------------------------------------------------------------
+  f32x16 acc[2][CB];     // accumulation registers
+  f32x16 s[2][2];        // [row block][token block] scores
+  uint32_t pw[2][2][8];  // [row block][token block] weights, bf16 pairs, as the B operand wants them
+  float m_run[2], l_run[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[qb][cb][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[qb][1][r] = -INFINITY;  // "previous tile": weights of zero
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pw[qb][1][i] = 0u;
+    m_run[qb] = kMinRef;
+    l_run[qb] = 0.f;
+  }
+  settle_a<CB>(acc);
+
+  load_tile(0);
+  store_tile(0, 0);
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));  // Q has arrived, and sits in accumulation registers
+  __syncthreads();
+
+  // two of a row block's 16 weights of a token block
+  auto weights_piece = [&](int blk, int qb, int i) {
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i], p.scale_log2, -m_run[qb]));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i + 1], p.scale_log2, -m_run[qb]));
+    pw[qb][blk][i] = pack_bf16x2(p0, p1);
+    l_run[qb] += p0 + p1;
+    // pin the piece here, between the matrix instructions around it (they are volatile statements too);
+    // otherwise the optimiser sinks the arithmetic towards its first use, out from under them
+    asm volatile("" : "+v"(pw[qb][blk][i]), "+v"(l_run[qb]));
+  };
+  auto rescale = [&](const float (&fac)[2]) {
+    if (__builtin_amdgcn_ballot_w64(fac[0] != 1.f || fac[1] != 1.f)) {
+      settle_a<CB>(acc);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) acc[qb][cb] *= fac[qb];
+      settle_a<CB>(acc);
+    }
+  };
+  // V^T fragment of 16-token step kq, channel block cb, from tile buffer vb
+  auto vt_frag = [&](int vb, int kq, int cb) {
+    const int ch = 32 * cb + n;
+    return *(const u32x4*)&sm.vt[vb][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3];
+  };
+
+  // One tile step; see the header for the phase order.  MASKED (compile time) adds the causal / length
+  // select to the two reference computations, the only place that looks at token positions.
+  int vcur = 0, vprev = 0;  // V^T buffers of this step's tile and of the one before (it % 3, (it - 1) % 3)
+  bool pending = false;     // the previous tile's second block still waits for its output product
+  auto tile_step = [&](int it, auto masked_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const int t0 = it * kBN, buf = it & 1;
+    const bool more = it + 1 < n_tiles;
+    if (more) load_tile(t0 + kBN);
+
+    // Softmax reference of one token block for both row blocks.  Register r of a score tile: token
+    // t0 + 32 blk + 8 (r/4) + 4 half + r%4.  Scores stay unscaled; the scale (> 0) is folded into
+    // the exponent: 2^(c s - m_ref).  The reference is raised (and the accumulators rescaled) only
+    // when some row's block maximum exceeds it by more than kSlack; each lane first tests its own 16
+    // tokens and the exchange with the lane holding the row's other 16 happens only then.
+    auto reference = [&](int blk, float (&fac)[2]) {
+      settle_v(s[0][blk], s[1][blk]);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
+        float m_blk = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = s[qb][blk][r];
+          if (MASKED) {
+            const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
+            v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
+            s[qb][blk][r] = v;
+          }
+          m_blk = fmaxf(m_blk, v);
+        }
+        fac[qb] = 1.f;
+        if (__builtin_amdgcn_ballot_w64(m_blk * p.scale_log2 > m_run[qb] + kSlack)) {
+          m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
+          const float m_cand = m_blk * p.scale_log2;
+          const float m_new = (m_cand > m_run[qb] + kSlack) ? m_cand : m_run[qb];
+          fac[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+          m_run[qb] = m_new;
+          l_run[qb] *= fac[qb];
+        }
+      }
+    };
+
+    if (t0 < wave_limit) {
+      const int vold = pending ? vprev : vcur;  // first step: weights are zero, any finite V will do
+      // fragment order: K block 0 | V^T of the previous tile's block 1 | K block 1 | V^T block 0
+      constexpr int G0 = KS, G1 = KS + 2 * CB, G2 = 2 * KS + 2 * CB, kFrags = 2 * KS + 4 * CB;
+      constexpr int kRing = 8;
+      u32x4 fr[kRing];
+      auto fetch = [&](auto fc) {
+        constexpr int f = decltype(fc)::value;
+        if constexpr (f < G0) {
+          fr[f % kRing] = *(const u32x4*)&sm.k[buf][n][16 * f + 8 * half];
+        } else if constexpr (f < G1) {
+          constexpr int j = f - G0;
+          fr[f % kRing] = vt_frag(vold, 2 + j / CB, j % CB);
+        } else if constexpr (f < G2) {
+          constexpr int ks = f - G1;
+          fr[f % kRing] = *(const u32x4*)&sm.k[buf][32 + n][16 * ks + 8 * half];
+        } else {
+          constexpr int j = f - G2;
+          fr[f % kRing] = vt_frag(vcur, j / CB, j % CB);
+        }
+      };
+      static_for<0, kRing>(fetch);
+      __builtin_amdgcn_sched_barrier(0);
+      float fac0[2], fac1[2];
+      static_for<0, kFrags>([&](auto fc) {
+        constexpr int f = decltype(fc)::value;
+        const u32x4 a = fr[f % kRing];
+        if constexpr (f < G0) {  // phase 1
+          if constexpr (f == 0) {
+            mfma_first_v(s[0][0], a, qf[0][0]);
+            mfma_first_v(s[1][0], a, qf[1][0]);
+          } else {
+            mfma_v(s[0][0], a, qf[0][f]);
+            mfma_v(s[1][0], a, qf[1][f]);
+          }
+        } else if constexpr (f < G1) {  // phase 2: previous tile's block 1
+          constexpr int j = f - G0, sh = (j / CB) * 4, cb = j % CB;
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+            mfma_a(acc[qb][cb], a, u32x4{pw[qb][1][sh], pw[qb][1][sh + 1], pw[qb][1][sh + 2], pw[qb][1][sh + 3]});
+        } else if constexpr (f < G2) {  // phase 3
+          constexpr int ks = f - G1;
+          if constexpr (ks == 0) {
+            mfma_first_v(s[0][1], a, qf[0][0]);
+            mfma_first_v(s[1][1], a, qf[1][0]);
+          } else {
+            mfma_v(s[0][1], a, qf[0][ks]);
+            mfma_v(s[1][1], a, qf[1][ks]);
+          }
+        } else {  // phase 4
+          constexpr int j = f - G2, sh = (j / CB) * 4, cb = j % CB;
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+            mfma_a(acc[qb][cb], a, u32x4{pw[qb][0][sh], pw[qb][0][sh + 1], pw[qb][0][sh + 2], pw[qb][0][sh + 3]});
+        }
+        if constexpr (f + kRing < kFrags) fetch(std::integral_constant<int, f + kRing>{});
+        // the softmax work that runs under this phase's matrix instructions
+        if constexpr (f < G0) {
+          constexpr int per = 8 / KS;
+#pragma unroll
+          for (int i = f * per; i < (f + 1) * per; ++i) weights_piece(1, 1, i);
+          if constexpr (f == G0 - 1) reference(0, fac0);
+        } else if constexpr (f < G1) {
+          constexpr int j = f - G0, per = 8 / (2 * CB);
+#pragma unroll
+          for (int i = j * per; i < (j + 1) * per; ++i) weights_piece(0, 0, i);
+          if constexpr (f == G1 - 1) rescale(fac0);
+        } else if constexpr (f < G2) {
+          constexpr int j = f - G1, per = 8 / KS;
+#pragma unroll
+          for (int i = j * per; i < (j + 1) * per; ++i) weights_piece(0, 1, i);
+          if constexpr (f == G2 - 1) reference(1, fac1);
+        } else {
+          constexpr int j = f - G2, per = 8 / (2 * CB);
+#pragma unroll
+          for (int i = j * per; i < (j + 1) * per; ++i) weights_piece(1, 0, i);
+          if constexpr (f == kFrags - 1) rescale(fac1);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep each fragment's softmax share next to its matrix instructions
+      });
+      pending = true;
+    }
+    const int vnext = vcur == 2 ? 0 : vcur + 1;
+    if (more) store_tile(buf ^ 1, vnext);
+    vprev = vcur;
+    vcur = vnext;
+    __syncthreads();
+  };
+  // The block that is still in flight after the last step a wavefront computes.
+  auto drain = [&]() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) weights_piece(1, 1, i);
+#pragma unroll
+    for (int j = 0; j < 2 * CB; ++j) {
+      const u32x4 a = vt_frag(vprev, 2 + j / CB, j % CB);
+      const int sh = (j / CB) * 4;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+        mfma_a(acc[qb][j % CB], a, u32x4{pw[qb][1][sh], pw[qb][1][sh + 1], pw[qb][1][sh + 2], pw[qb][1][sh + 3]});
+    }
+    pending = false;
+  };
+
+  // tiles wholly visible to every row of this wavefront need no mask; tiles past its last row are
+  // staging only -- the pending block is finished before the first of those overwrites its buffer
+  int n_plain = p.S_k / kBN;
+  if (p.causal) {
+    const int vis = (r0 + off + 1) / kBN;  // tiles entirely at or before the first row's limit
+    n_plain = vis < n_plain ? vis : n_plain;
+  }
+  n_plain = n_plain < n_tiles ? n_plain : n_tiles;
+  int n_compute = wave_limit > 0 ? (wave_limit + kBN - 1) / kBN : 0;
+  n_compute = n_compute < n_tiles ? n_compute : n_tiles;
+  n_plain = n_plain < n_compute ? n_plain : n_compute;
+  int it = 0;
+  for (; it < n_plain; ++it) tile_step(it, std::false_type{});
+  for (; it < n_compute; ++it) tile_step(it, std::true_type{});
+  if (pending) drain();
+  for (; it < n_tiles; ++it) tile_step(it, std::true_type{});  // staging only (t0 >= wave_limit)
+
+  // ---- write this wavefront's rows: lane (half, n), acc[qb][cb][r] = row 32 qb + n, channel
+  //      32 cb + 8 (r/4) + 4 half + r%4.  Both halves hold the full row sum after the exchange.
+  settle_a<CB>(acc);
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int my_row = r0 + 32 * qb + n;
+    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+    if (my_row < p.S_q) {
+      const float inv = 1.f / l;
+      uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * DV;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
+          w[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
+          *(u32x2*)(orow + 32 * cb + 8 * q4 + 4 * half) = w;
+        }
+      if (half == 0 && p.lse_out)
+        p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
+    }
+  }
+}
+
+template <int DQK, int DV>
+hipError_t launch64(const PrefillParams& p, hipStream_t s) {
+  const int n_qtiles = (p.S_q + 255) / 256;
+  const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
+  if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+  const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
+  prefill_mfma64_kernel<DQK, DV><<<dim3((unsigned)n_wg), dim3(256), 0, s>>>(p, n_qtiles, xcd_aware);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_prefill_mfma64(const PrefillParams& p, hipStream_t s) {
+  if (p.B == 0) return hipSuccess;
+  if (p.d_qk == 128) return launch64<128, 128>(p, s);
+  if (p.d_v == 128) return launch64<64, 128>(p, s);
+  return launch64<64, 64>(p, s);
+}
+
+}  // namespace diffqkv
