@@ -73,7 +73,8 @@ typedef struct {
 typedef struct {
   int32_t decode_chunk_tokens; /* tokens per context split (multiple of 128)                      */
   int32_t force_generic;       /* 1: always take the portable kernels instead of the MFMA ones    */
-  int32_t prefill_waves;       /* wavefronts per workgroup in the MFMA prefill: 4 or 8           */
+  int32_t prefill_waves;       /* MFMA prefill variant: 0 choose; 8 or 4 wavefronts of 32 rows;  *
+                                * 2 = 4 wavefronts of 64 rows (d_qk = d_v = 128 only)             */
   int32_t decode_ragged_mode;  /* work split of the MFMA decode kernel.  0: equal slices per
                                   wavefront when seqlens is given, fixed-size chunks otherwise;
                                   1: equal slices always; 2: fixed-size chunks always            */

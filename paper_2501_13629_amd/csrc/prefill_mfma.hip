@@ -347,7 +347,7 @@ bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
 }
 
 namespace {
-int g_prefill_waves = 8;  // 8: 8 wavefronts x 32 rows; 4: 4 x 32; 2: the 64-rows-per-wavefront kernel
+int g_prefill_waves = 0;  // 0: choose; 8: 8 wavefronts x 32 rows; 4: 4 x 32; 2: the 64-rows-per-wavefront kernel
 template <int DQK, int DV, int NW, int QB>
 hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
   constexpr int kBM = NW * 32 * QB;
@@ -360,13 +360,14 @@ hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
 }
 template <int DQK, int DV>
 hipError_t launch_variant(const PrefillParams& p, hipStream_t s) {
-  if (g_prefill_waves == 2) return launch_prefill_mfma64(p, s);
+  if ((g_prefill_waves == 0 || g_prefill_waves == 2) && prefill_mfma64_supported(p, 1))
+    return launch_prefill_mfma64(p, s);
   if (g_prefill_waves == 4) return launch_nw<DQK, DV, 4, 1>(p, s);
   return launch_nw<DQK, DV, 8, 1>(p, s);
 }
 }  // namespace
 
-void set_prefill_waves(int nw) { g_prefill_waves = (nw == 4 || nw == 2) ? nw : 8; }
+void set_prefill_waves(int nw) { g_prefill_waves = (nw == 2 || nw == 4 || nw == 8) ? nw : 0; }
 
 hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s) {
   if (p.B == 0) return hipSuccess;

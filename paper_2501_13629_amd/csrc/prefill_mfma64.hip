@@ -73,6 +73,7 @@ struct Smem64 {
 
 template <int DQK, int DV>
 __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p, int n_qtiles, int xcd_aware) {
+  static_assert(DQK == 128 && DV == 128, "the slot schedule below is laid out for four phases of eight fragments");
   constexpr int KS = DQK / 16;  // k-steps of the score product (16 channels each)
   constexpr int CB = DV / 32;   // 32-channel blocks of the output
   constexpr int kThreads = 256;
@@ -131,35 +132,43 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
   const int v_voff = (4 * v_tq) * (DV * 2) + v_c8 * 16;
   u32x4 kst[KLD], vst[4];
-  auto load_tile = [&](int t0) {
+  auto load_k_tile = [&](int t0) {
 #pragma unroll
     for (int i = 0; i < KLD; ++i)
       kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kThreads + tid) * 16, t0 * (DQK * 2), 0);
+  };
+  auto load_v_tile = [&](int t0) {
     if (v_role) {
 #pragma unroll
       for (int x = 0; x < 4; ++x)
         vst[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2), t0 * (DV * 2), 0);
     }
   };
-  auto store_tile = [&](int buf, int vbuf) {
-#pragma unroll
-    for (int i = 0; i < KLD; ++i) {
-      const int piece = i * kThreads + tid;
-      *(u32x4*)&sm.k[buf][piece / (DQK / 8)][(piece % (DQK / 8)) * 8] = kst[i];
-    }
+  auto load_tile = [&](int t0) {
+    load_k_tile(t0);
+    load_v_tile(t0);
+  };
+  auto store_k_item = [&](int i, int buf) {  // i in [0, KLD)
+    const int piece = i * kThreads + tid;
+    *(u32x4*)&sm.k[buf][piece / (DQK / 8)][(piece % (DQK / 8)) * 8] = kst[i];
+  };
+  auto store_v_item = [&](int e, int vbuf) {  // channel e in [0, 8) of this thread's chunk
     if (v_role) {
       const int pos = vt_pos(4 * v_tq);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        // channel e of the chunk: word e/2, low or high half, from the 4 tokens
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 w;
-        w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
-        w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
-        const int ch = v_c8 * 8 + e;
-        *(u32x2*)&sm.vt[vbuf][ch][(((pos >> 3) ^ vt_swizzle(ch)) << 3) + (pos & 7)] = w;
-      }
+      // word e/2, low or high half, from the 4 tokens
+      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+      u32x2 w;
+      w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
+      w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
+      const int ch = v_c8 * 8 + e;
+      *(u32x2*)&sm.vt[vbuf][ch][(((pos >> 3) ^ vt_swizzle(ch)) << 3) + (pos & 7)] = w;
     }
+  };
+  auto store_tile = [&](int buf, int vbuf) {
+#pragma unroll
+    for (int i = 0; i < KLD; ++i) store_k_item(i, buf);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) store_v_item(e, vbuf);
   };
 
   // ---- state ----------------------------------------------------------------------------------------
@@ -184,6 +193,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
 
   load_tile(0);
   store_tile(0, 0);
+  if (n_tiles > 1) load_tile(kBN);  // staging registers always hold the tile after the one in LDS
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -196,9 +206,24 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i + 1], p.scale_log2, -m_run[qb]));
     pw[qb][blk][i] = pack_bf16x2(p0, p1);
     l_run[qb] += p0 + p1;
-    // pin the piece here, between the matrix instructions around it (they are volatile statements too);
-    // otherwise the optimiser sinks the arithmetic towards its first use, out from under them
-    asm volatile("" : "+v"(pw[qb][blk][i]), "+v"(l_run[qb]));
+  };
+  // The same in two halves, numbered h = 0..31 per token block: groups of eight halves cover pieces
+  // 0-3 of row block 0, 0-3 of row block 1, 4-7 of row block 0, 4-7 of row block 1; an even half
+  // takes the two exponentials of its piece, the odd half after it packs and sums them.  Each half
+  // is pinned where it is written, between the (volatile) matrix instructions around it; otherwise
+  // the optimiser sinks the arithmetic towards its first use, out from under them.
+  auto weights_half = [&](auto blkc, auto hc, float (&tp)[2]) {
+    constexpr int blk = decltype(blkc)::value, h = decltype(hc)::value;
+    constexpr int group = h / 8, qb = group & 1, i = (group >> 1) * 4 + (h % 8) / 2;
+    if constexpr (h % 2 == 0) {
+      tp[0] = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i], p.scale_log2, -m_run[qb]));
+      tp[1] = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i + 1], p.scale_log2, -m_run[qb]));
+      asm volatile("" : "+v"(tp[0]), "+v"(tp[1]));
+    } else {
+      pw[qb][blk][i] = pack_bf16x2(tp[0], tp[1]);
+      l_run[qb] += tp[0] + tp[1];
+      asm volatile("" : "+v"(pw[qb][blk][i]), "+v"(l_run[qb]));
+    }
   };
   auto rescale = [&](const float (&fac)[2]) {
     if (__builtin_amdgcn_ballot_w64(fac[0] != 1.f || fac[1] != 1.f)) {
@@ -223,41 +248,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   auto tile_step = [&](int it, auto masked_tag) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int t0 = it * kBN, buf = it & 1;
-    const bool more = it + 1 < n_tiles;
-    if (more) load_tile(t0 + kBN);
-
-    // Softmax reference of one token block for both row blocks.  Register r of a score tile: token
-    // t0 + 32 blk + 8 (r/4) + 4 half + r%4.  Scores stay unscaled; the scale (> 0) is folded into
-    // the exponent: 2^(c s - m_ref).  The reference is raised (and the accumulators rescaled) only
-    // when some row's block maximum exceeds it by more than kSlack; each lane first tests its own 16
-    // tokens and the exchange with the lane holding the row's other 16 happens only then.
-    auto reference = [&](int blk, float (&fac)[2]) {
-      settle_v(s[0][blk], s[1][blk]);
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
-        float m_blk = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[qb][blk][r];
-          if (MASKED) {
-            const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
-            v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
-            s[qb][blk][r] = v;
-          }
-          m_blk = fmaxf(m_blk, v);
-        }
-        fac[qb] = 1.f;
-        if (__builtin_amdgcn_ballot_w64(m_blk * p.scale_log2 > m_run[qb] + kSlack)) {
-          m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
-          const float m_cand = m_blk * p.scale_log2;
-          const float m_new = (m_cand > m_run[qb] + kSlack) ? m_cand : m_run[qb];
-          fac[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-          m_run[qb] = m_new;
-          l_run[qb] *= fac[qb];
-        }
-      }
-    };
+    const bool more = it + 1 < n_tiles, more2 = it + 2 < n_tiles;
+    const int vnext = vcur == 2 ? 0 : vcur + 1;
 
     if (t0 < wave_limit) {
       const int vold = pending ? vprev : vcur;  // first step: weights are zero, any finite V will do
@@ -283,66 +275,118 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       static_for<0, kRing>(fetch);
       __builtin_amdgcn_sched_barrier(0);
       float fac0[2], fac1[2];
+      float mb[2];  // block maximum of the reference in progress
+      float tp[2];  // exponentials waiting to be packed by the next half
+
+      // A wavefront issues in order; the matrix pipe takes one instruction per 32 cycles and holds
+      // the vector ALU's operand ports for a good part of them, so two matrix instructions back to
+      // back, or a long run of vector work, both leave one of the pipes idle.  Every matrix
+      // instruction is therefore followed by a "slot" with an even share of all the other work of
+      // the step.  Slots are numbered g = 0..63 (phase p covers 16 p .. 16 p + 15):
+      //   reference of block 0 in four chunks at g = 16..19, of block 1 at g = 48..51 (the matrix
+      //   instructions of phases 2 and 4 do not depend on them);
+      //   the weights of a token block as 32 half-pieces -- even: two exponentials, odd: pack and sum
+      //   -- for block 0 at g = 20..47, for block 1 at g = 52..63 and on into g = 0..15 of the next
+      //   step (28 slots: the first four take two halves each); row block 0 / 1 alternate in groups
+      //   of four pieces so that everything is ready when the output product asks for it;
+      //   staging (LDS stores of the next tile, then the loads of the one after) on odd slots.
+      // Softmax reference: register r of a score tile is token t0 + 32 blk + 8 (r/4) + 4 half + r%4.
+      // Scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - m_ref).  The
+      // reference is raised (and the accumulators rescaled) only when some row's block maximum
+      // exceeds it by more than kSlack; each lane first tests its own 16 tokens and the exchange
+      // with the lane holding the row's other 16 happens only then.
+      auto reference_chunk = [&](auto blkc, auto cc, float (&fac)[2]) {
+        constexpr int blk = decltype(blkc)::value, c = decltype(cc)::value;
+        constexpr int qb = c / 2, part = c % 2;
+        if constexpr (c == 0) settle_v(s[0][blk], s[1][blk]);
+        const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
+        float m_blk = part == 0 ? -INFINITY : mb[qb];
+#pragma unroll
+        for (int r = part * 8; r < (part + 1) * 8; ++r) {
+          float v = s[qb][blk][r];
+          if (MASKED) {
+            const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
+            v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
+            s[qb][blk][r] = v;
+          }
+          m_blk = fmaxf(m_blk, v);
+        }
+        mb[qb] = m_blk;
+        if constexpr (part == 1) {
+          fac[qb] = 1.f;
+          if (__builtin_amdgcn_ballot_w64(m_blk * p.scale_log2 > m_run[qb] + kSlack)) {
+            m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
+            const float m_cand = m_blk * p.scale_log2;
+            const float m_new = (m_cand > m_run[qb] + kSlack) ? m_cand : m_run[qb];
+            fac[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+            m_run[qb] = m_new;
+            l_run[qb] *= fac[qb];
+          }
+        } else {
+          asm volatile("" : "+v"(mb[qb]));  // pinned to its slot
+        }
+      };
+      auto stage_item = [&](auto ic) {
+        constexpr int idx = decltype(ic)::value;
+        // (unconditional: past the last tile the stores park stale registers in a buffer nobody
+        //  reads, and the loads fall outside the buffer resource and return zeros)
+        if constexpr (idx < KLD) store_k_item(idx, buf ^ 1);
+        else if constexpr (idx < KLD + 8) store_v_item(idx - KLD, vnext);
+        else if constexpr (idx == KLD + 8) load_k_tile(t0 + 2 * kBN);
+        else load_v_tile(t0 + 2 * kBN);
+      };
+      auto slot = [&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        if constexpr (g >= 16 && g < 20) reference_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, g - 16>{}, fac0);
+        if constexpr (g >= 48 && g < 52) reference_chunk(std::integral_constant<int, 1>{}, std::integral_constant<int, g - 48>{}, fac1);
+        if constexpr (g >= 20 && g < 24) {
+          weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * (g - 20)>{}, tp);
+          weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * (g - 20) + 1>{}, tp);
+        }
+        if constexpr (g >= 24 && g < 48) weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 8 + g - 24>{}, tp);
+        if constexpr (g >= 52 && g < 56) {
+          weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (g - 52)>{}, tp);
+          weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (g - 52) + 1>{}, tp);
+        }
+        if constexpr (g >= 56) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 8 + g - 56>{}, tp);
+        if constexpr (g < 16) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 16 + g>{}, tp);
+        if constexpr ((g & 1) && g < 16) stage_item(std::integral_constant<int, g / 2>{});
+        if constexpr ((g & 1) && g >= 25 && g < 25 + 2 * (KLD + 10 - 8)) stage_item(std::integral_constant<int, 8 + (g - 25) / 2>{});
+      };
+
       static_for<0, kFrags>([&](auto fc) {
         constexpr int f = decltype(fc)::value;
+        constexpr int phase = f / 8 + 1, j = f % 8;  // step inside the phase
         const u32x4 a = fr[f % kRing];
-        if constexpr (f < G0) {  // phase 1
-          if constexpr (f == 0) {
-            mfma_first_v(s[0][0], a, qf[0][0]);
-            mfma_first_v(s[1][0], a, qf[1][0]);
+        auto matrix = [&](auto qc) {
+          constexpr int qb = decltype(qc)::value;
+          if constexpr (phase == 1 || phase == 3) {
+            constexpr int blk = phase == 1 ? 0 : 1;
+            if constexpr (j == 0) mfma_first_v(s[qb][blk], a, qf[qb][0]);
+            else mfma_v(s[qb][blk], a, qf[qb][j]);
           } else {
-            mfma_v(s[0][0], a, qf[0][f]);
-            mfma_v(s[1][0], a, qf[1][f]);
+            constexpr int blk = phase == 2 ? 1 : 0, sh = (j / CB) * 4, cb = j % CB;
+            mfma_a(acc[qb][cb], a, u32x4{pw[qb][blk][sh], pw[qb][blk][sh + 1], pw[qb][blk][sh + 2], pw[qb][blk][sh + 3]});
           }
-        } else if constexpr (f < G1) {  // phase 2: previous tile's block 1
-          constexpr int j = f - G0, sh = (j / CB) * 4, cb = j % CB;
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            mfma_a(acc[qb][cb], a, u32x4{pw[qb][1][sh], pw[qb][1][sh + 1], pw[qb][1][sh + 2], pw[qb][1][sh + 3]});
-        } else if constexpr (f < G2) {  // phase 3
-          constexpr int ks = f - G1;
-          if constexpr (ks == 0) {
-            mfma_first_v(s[0][1], a, qf[0][0]);
-            mfma_first_v(s[1][1], a, qf[1][0]);
-          } else {
-            mfma_v(s[0][1], a, qf[0][ks]);
-            mfma_v(s[1][1], a, qf[1][ks]);
-          }
-        } else {  // phase 4
-          constexpr int j = f - G2, sh = (j / CB) * 4, cb = j % CB;
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            mfma_a(acc[qb][cb], a, u32x4{pw[qb][0][sh], pw[qb][0][sh + 1], pw[qb][0][sh + 2], pw[qb][0][sh + 3]});
-        }
+        };
+        matrix(std::integral_constant<int, 0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        slot(std::integral_constant<int, 2 * f>{});
+        __builtin_amdgcn_sched_barrier(0);
+        matrix(std::integral_constant<int, 1>{});
+        __builtin_amdgcn_sched_barrier(0);
         if constexpr (f + kRing < kFrags) fetch(std::integral_constant<int, f + kRing>{});
-        // the softmax work that runs under this phase's matrix instructions
-        if constexpr (f < G0) {
-          constexpr int per = 8 / KS;
-#pragma unroll
-          for (int i = f * per; i < (f + 1) * per; ++i) weights_piece(1, 1, i);
-          if constexpr (f == G0 - 1) reference(0, fac0);
-        } else if constexpr (f < G1) {
-          constexpr int j = f - G0, per = 8 / (2 * CB);
-#pragma unroll
-          for (int i = j * per; i < (j + 1) * per; ++i) weights_piece(0, 0, i);
-          if constexpr (f == G1 - 1) rescale(fac0);
-        } else if constexpr (f < G2) {
-          constexpr int j = f - G1, per = 8 / KS;
-#pragma unroll
-          for (int i = j * per; i < (j + 1) * per; ++i) weights_piece(0, 1, i);
-          if constexpr (f == G2 - 1) reference(1, fac1);
-        } else {
-          constexpr int j = f - G2, per = 8 / (2 * CB);
-#pragma unroll
-          for (int i = j * per; i < (j + 1) * per; ++i) weights_piece(1, 0, i);
-          if constexpr (f == kFrags - 1) rescale(fac1);
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keep each fragment's softmax share next to its matrix instructions
+        slot(std::integral_constant<int, 2 * f + 1>{});
+        // accumulators gathered under the old reference are rescaled once their phase is complete
+        if constexpr (f == G1 - 1) rescale(fac0);
+        if constexpr (f == kFrags - 1) rescale(fac1);
+        __builtin_amdgcn_sched_barrier(0);
       });
       pending = true;
+    } else {
+      if (more) store_tile(buf ^ 1, vnext);
+      if (more2) load_tile(t0 + 2 * kBN);
     }
-    const int vnext = vcur == 2 ? 0 : vcur + 1;
-    if (more) store_tile(buf ^ 1, vnext);
     vprev = vcur;
     vcur = vnext;
     __syncthreads();
@@ -350,7 +394,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   // The block that is still in flight after the last step a wavefront computes.
   auto drain = [&]() {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) weights_piece(1, 1, i);
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i = 4; i < 8; ++i) weights_piece(1, qb, i);  // the halves the next step would have taken
 #pragma unroll
     for (int j = 0; j < 2 * CB; ++j) {
       const u32x4 a = vt_frag(vprev, 2 + j / CB, j % CB);
@@ -416,11 +462,14 @@ hipError_t launch64(const PrefillParams& p, hipStream_t s) {
 
 }  // namespace
 
+bool prefill_mfma64_supported(const PrefillParams& p, int dtype) {
+  // (the staging loads run up to two tiles past the end of a head: keep them inside the 32-bit offset)
+  return dtype == 1 && p.d_qk == 128 && p.d_v == 128 && (int64_t)(p.S_k + 2 * kBN) * 128 * 2 < (1ll << 31);
+}
+
 hipError_t launch_prefill_mfma64(const PrefillParams& p, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
-  if (p.d_qk == 128) return launch64<128, 128>(p, s);
-  if (p.d_v == 128) return launch64<64, 128>(p, s);
-  return launch64<64, 64>(p, s);
+  return launch64<128, 128>(p, s);
 }
 
 }  // namespace diffqkv

@@ -17,9 +17,9 @@ def _reset_tuning():
     binding.diffqkv_set_tuning()
 
 
-def run(cfg, causal=True, rows=None, force_generic=False):
+def run(cfg, causal=True, rows=None, force_generic=False, variant=0):
     d = inputs.make_prefill(cfg)
-    binding.diffqkv_set_tuning(force_generic=force_generic)
+    binding.diffqkv_set_tuning(force_generic=force_generic, prefill_waves=variant)
     out, lse = binding.diffqkv_prefill(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]), causal=causal,
                                        want_lse=True)
     torch.cuda.synchronize()
@@ -49,6 +49,18 @@ def test_prefix_plus_chunk_and_noncausal(dtype):
     cfg = inputs.config("prefill_8k", B=1, S=200, S_k=517, dtype=dtype, index=70)
     run(cfg, causal=True)
     run(cfg, causal=False)
+
+
+@pytest.mark.parametrize("variant", [2, 4, 8])
+def test_every_mfma_variant(variant):
+    """The three matrix-core kernels (64 rows per wavefront; 4 or 8 wavefronts of 32 rows) on lengths that
+    end inside a tile, a wavefront's rows and a workgroup's rows, with and without a cached prefix."""
+    for S in (1, 63, 64, 65, 255, 256, 257, 700, 1100):
+        run(inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, S=S, index=73 + S % 7), variant=variant)
+    cfg = inputs.config("prefill_8k", B=2, n_q=4, n_k=2, n_v=2, S=300, S_k=1000, index=74)
+    run(cfg, causal=True, variant=variant)
+    run(cfg, causal=False, variant=variant)
+    run(inputs.config("prefill_8k", B=1, n_q=2, n_k=1, n_v=1, S=130, S_k=131, index=75), variant=variant)
 
 
 def test_generic_kernel_matches_too():
