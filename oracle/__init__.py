@@ -121,7 +121,7 @@ def decode(q, k_cache, v_cache, seqlens=None, scale=None, T=None):
     return out, lse
 
 
-def decode_topk(q, k_cache, v_cache, top_k, seqlens=None, scale=None, T=None, renormalize=False):
+def decode_topk(q, k_cache, v_cache, top_k, seqlens=None, scale=None, T=None, renormalize=True):
     """Selective V-cache fetching: weights from the softmax over all T positions, output from the
     `top_k` previous positions of largest weight plus the current token (position T_b - 1).
     Returns (out [B,n_q,d_v], lse [B,n_q], selected int32 [B,n_q,top_k+1] padded with -1)."""

@@ -254,7 +254,7 @@ def diffqkv_prefill(q, k, v, causal=True, scale=None, out=None, lse_out=None, wa
     return (out, lse_out) if (want_lse or lse_out is not None) else out
 
 
-def diffqkv_decode_topk(q, k_cache, v_cache, top_k, seqlens=None, T=None, scale=None, renormalize=False, out=None,
+def diffqkv_decode_topk(q, k_cache, v_cache, top_k, seqlens=None, T=None, scale=None, renormalize=True, out=None,
                         workspace=None, want_lse=False, want_selection=False):
     """Decode with selective V fetching: softmax over all positions, output from the top_k previous
     positions of largest weight plus the current token.  Returns out[, lse][, selection]."""
@@ -290,7 +290,7 @@ def diffqkv_decode_topk(q, k_cache, v_cache, top_k, seqlens=None, T=None, scale=
     return res[0] if len(res) == 1 else tuple(res)
 
 
-def diffqkv_decode_topk_paged(q, k_pool, v_pool, block_table, seqlens, top_k, scale=None, renormalize=False,
+def diffqkv_decode_topk_paged(q, k_pool, v_pool, block_table, seqlens, top_k, scale=None, renormalize=True,
                               out=None, workspace=None, want_lse=False, want_selection=False):
     """Paged variant of diffqkv_decode_topk."""
     _dev(q, k_pool, v_pool, block_table, seqlens, out, workspace)

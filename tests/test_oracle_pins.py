@@ -350,9 +350,12 @@ def test_topk_ties_go_to_the_lower_position_and_current_token_always_counts():
     q = rnd((1, 2, 8), 56)
     k = np.ones((1, 1, 10, 8), np.float32)
     v = rnd((1, 1, 10, 4), 57)
-    out, _, sel = oracle.decode_topk(q, k, v, 3)
+    out, _, sel = oracle.decode_topk(q, k, v, 3, renormalize=False)
     assert list(sel[0, 0]) == [0, 1, 2, 9]
     rel_close(out[0, 0], v[0, 0, [0, 1, 2, 9]].astype(np.float64).sum(axis=0) / 10.0)
+    out, _, sel = oracle.decode_topk(q, k, v, 3, renormalize=True)  # four equal weights: their mean
+    assert list(sel[0, 0]) == [0, 1, 2, 9]
+    rel_close(out[0, 0], v[0, 0, [0, 1, 2, 9]].astype(np.float64).mean(axis=0))
     # renormalised weights sum to one: constant V comes back unchanged; unnormalised: scaled by the kept mass
     vc = np.full((1, 1, 10, 4), 2.5, np.float32)
     rel_close(oracle.decode_topk(q, k, vc, 3, renormalize=True)[0], np.full((1, 2, 4), 2.5))
