@@ -244,10 +244,16 @@ def cpu_baseline(cfg, host, kind, kv_bytes, topk=-1):
         fn = lambda: oracle.prefill(a(host["q"]), a(host["k"]), a(host["v"]), causal=True, rows=rows)
         work = float(sum(4.0 * cfg["d_qk"] * cfg["B"] * cfg["n_q"] * (int(i) + 1) for i in rows)) / 1e12
         unit, sample = "TFLOP/s", "every 128th query row of every head (%d rows), one evaluation" % len(rows)
-    t0 = time.perf_counter()
-    fn()
-    dt = time.perf_counter() - t0
-    return {"value": round(work / dt, 4), "unit": unit, "cores": threads, "kind": "oracle", "sample": sample,
+    # repeat the sample until about ten seconds of CPU work have been timed (at least one evaluation)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        fn()
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or reps >= 1000:
+            break
+    sample = sample.replace("one evaluation", "%d evaluation%s" % (reps, "" if reps == 1 else "s"))
+    return {"value": round(work * reps / dt, 4), "unit": unit, "cores": threads, "kind": "oracle", "sample": sample,
             "seconds": round(dt, 3)}
 
 
