@@ -57,6 +57,8 @@ def _load():
         lib.oracle_lse_merge.argtypes = [i32, i32, vp, vp, vp, vp]
         lib.oracle_decode_topk.restype = i32
         lib.oracle_decode_topk.argtypes = [i32] * 7 + [f64] + [vp] * 3 + [i64] * 6 + [vp, i32, i32, i32, vp, vp, vp]
+        lib.oracle_augment_q.restype = i32
+        lib.oracle_augment_q.argtypes = [i32] * 4 + [vp] * 5
         lib.oracle_num_threads.restype = i32
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -267,3 +269,19 @@ def append_paged(k_new, v_new, k_pool, v_pool, block_table, positions):
             for c in range(d_v):
                 v_out[page, h, slot, c] = v_new[b, h, c]
     return k_out, v_out
+
+
+def augment_q(x, w_gate, w_up, w_down):
+    """Augmented Q (observations 3-4, section 2): x [M, hidden] -> W_down(silu(W_gate x) * (W_up x)).
+    w_gate, w_up [inter, hidden]; w_down [hidden, inter].  Returns float64 [M, hidden]."""
+    code = _dtype_code(x)
+    assert _dtype_code(w_gate) == code and _dtype_code(w_up) == code and _dtype_code(w_down) == code
+    x, w_gate, w_up, w_down = (np.ascontiguousarray(a) for a in (x, w_gate, w_up, w_down))
+    M, hidden = x.shape
+    inter = w_gate.shape[0]
+    assert w_gate.shape == (inter, hidden) and w_up.shape == (inter, hidden) and w_down.shape == (hidden, inter)
+    out = np.empty((M, hidden), dtype=np.float64)
+    rc = _load().oracle_augment_q(code, M, hidden, inter, _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_augment_q rejected its arguments")
+    return out

@@ -396,6 +396,40 @@ int oracle_decode_topk(int dtype, int B, int n_q, int n_k, int n_v, int d_qk, in
   return 0;
 }
 
+/* Augmented Q (observations 3-4 of section 2; the appendix's attention listing): the output of the
+ * query projection, one vector of `hidden` numbers per token, passes through a gated feed-forward
+ * of intermediate width `inter` before the heads are formed:
+ *     q' = W_down ( act(W_gate q) * (W_up q) ),    act = SiLU, z / (1 + exp(-z)), no biases.
+ * Weights in the layout of a linear layer, [out features][in features]: w_gate, w_up [inter][hidden],
+ * w_down [hidden][inter].  x [M][hidden]; out [M][hidden] in double.  Everything is evaluated in
+ * double with no intermediate rounding. */
+int oracle_augment_q(int dtype, int M, int hidden, int inter, const void* x, const void* w_gate,
+                     const void* w_up, const void* w_down, double* out) {
+  if (M < 0 || hidden <= 0 || inter <= 0) return -1;
+#pragma omp parallel for schedule(dynamic)
+  for (int m = 0; m < M; ++m) {
+    double* xin = (double*)malloc(sizeof(double) * (size_t)hidden);
+    double* mid = (double*)malloc(sizeof(double) * (size_t)inter);
+    for (int c = 0; c < hidden; ++c) xin[c] = load_elem(x, dtype, (int64_t)m * hidden + c);
+    for (int i = 0; i < inter; ++i) {
+      double gate = 0.0, up = 0.0;
+      for (int c = 0; c < hidden; ++c) {
+        gate += load_elem(w_gate, dtype, (int64_t)i * hidden + c) * xin[c];
+        up += load_elem(w_up, dtype, (int64_t)i * hidden + c) * xin[c];
+      }
+      mid[i] = gate / (1.0 + exp(-gate)) * up;
+    }
+    for (int j = 0; j < hidden; ++j) {
+      double y = 0.0;
+      for (int i = 0; i < inter; ++i) y += load_elem(w_down, dtype, (int64_t)j * inter + i) * mid[i];
+      out[(int64_t)m * hidden + j] = y;
+    }
+    free(xin);
+    free(mid);
+  }
+  return 0;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int oracle_num_threads(void) { return omp_get_max_threads(); }

@@ -365,3 +365,57 @@ def test_topk_ties_go_to_the_lower_position_and_current_token_always_counts():
     k2[0, 0, 9] = -50.0 * np.sign(q[0, 0])
     _, _, sel2 = oracle.decode_topk(q, k2, v, 2)
     assert 9 in list(sel2[0, 0]) and 9 in list(sel2[0, 1])
+
+
+# ---- augmented Q (observations 3-4 of section 2; the appendix's attention listing) -------------------
+
+def _augq_case(M, hidden, inter, seed):
+    return (rnd((M, hidden), seed), rnd((inter, hidden), seed + 1) / np.float32(np.sqrt(hidden)),
+            rnd((inter, hidden), seed + 2) / np.float32(np.sqrt(hidden)),
+            rnd((hidden, inter), seed + 3) / np.float32(np.sqrt(inter)))
+
+
+def test_augq_matches_library_linear_and_silu():
+    x, wg, wu, wd = _augq_case(5, 24, 40, 80)
+    t = lambda a: torch.from_numpy(a.astype(np.float64))
+    F = torch.nn.functional
+    want = F.linear(F.silu(F.linear(t(x), t(wg))) * F.linear(t(x), t(wu)), t(wd)).numpy()
+    rel_close(oracle.augment_q(x, wg, wu, wd), want)
+
+
+def test_augq_brute_force_loops():
+    x, wg, wu, wd = _augq_case(2, 3, 4, 84)
+    want = np.zeros((2, 3))
+    for m in range(2):
+        mid = []
+        for i in range(4):
+            g = sum(float(wg[i, c]) * float(x[m, c]) for c in range(3))
+            u = sum(float(wu[i, c]) * float(x[m, c]) for c in range(3))
+            mid.append(g / (1.0 + math.exp(-g)) * u)
+        for j in range(3):
+            want[m, j] = sum(float(wd[j, i]) * mid[i] for i in range(4))
+    rel_close(oracle.augment_q(x, wg, wu, wd), want)
+
+
+def test_augq_closed_forms():
+    x, wg, wu, wd = _augq_case(3, 8, 8, 88)
+    # a zero gate closes everything: silu(0) = 0
+    assert np.all(oracle.augment_q(x, np.zeros_like(wg), wu, wd) == 0.0)
+    # identity up and down projections leave silu(W_gate x) * x
+    eye = np.eye(8, dtype=np.float32)
+    g = wg.astype(np.float64) @ x.astype(np.float64).T
+    rel_close(oracle.augment_q(x, wg, eye, eye), (g / (1.0 + np.exp(-g))).T * x.astype(np.float64))
+    # linear in W_up and in W_down, not in W_gate; gate and up are not interchangeable
+    base = oracle.augment_q(x, wg, wu, wd)
+    rel_close(oracle.augment_q(x, wg, 2 * wu, wd), 2 * base)
+    rel_close(oracle.augment_q(x, wg, wu, -4 * wd), -4 * base)  # (powers of two: exact in fp32)
+    assert np.max(np.abs(oracle.augment_q(x, wu, wg, wd) - base)) > 1e-3
+    # a large gate passes the up branch through: silu(z) -> z
+    big = oracle.augment_q(x, 1000 * eye, eye, eye)
+    xp = x.astype(np.float64)
+    rel_close(big[xp > 0.05], (1000 * xp * xp)[xp > 0.05], tol=1e-9)
+    # bf16 inputs are widened exactly
+    xb = (x.view(np.uint32) >> 16).astype(np.uint16)
+    wb = [(w.view(np.uint32) >> 16).astype(np.uint16) for w in (wg, wu, wd)]
+    widen = lambda b: (b.astype(np.uint32) << 16).view(np.float32)
+    rel_close(oracle.augment_q(xb, *wb), oracle.augment_q(widen(xb), *[widen(w) for w in wb]))
