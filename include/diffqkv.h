@@ -211,6 +211,34 @@ int diffqkv_append_paged(const diffqkv_shape* shape /* host */, const void* k_ne
                          void* hip_stream);
 
 /*
+ * Augmented Q (observations 3-4 of section 2, "Formulation of DiffQKV Attention"; the attention
+ * listing of the appendix): the output of the query projection, one vector of `hidden` numbers per
+ * token, passes through a gated feed-forward of width `inter` before the heads are formed:
+ *     q_out = W_down ( silu(W_gate q_in) * (W_up q_in) ),   silu(z) = z / (1 + exp(-z)),  no biases.
+ * (Sigma: hidden 2048 / inter 3072 and 4096 / 6144.)  The attention kernels above are unaffected:
+ * they receive q_out, reshaped to [n_q, d_qk] per token and rotated, as their q.
+ *
+ * Device pointers, all contiguous and 16-byte aligned, all of `dtype`:
+ *   q_in [M, hidden], w_gate and w_up [inter, hidden], w_down [hidden, inter] (the layout of a linear
+ *   layer: [out features][in features]), q_out [M, hidden] (may not alias q_in).
+ * hidden and inter must be multiples of 8.  M is the number of tokens of the step (the batch size in
+ * decode); the matrix-core path (bf16, widths that are multiples of 1024) is laid out for M <= 16 per
+ * pass and repeats the pass for more.  Accumulation is fp32; the intermediate activations are rounded
+ * once to `dtype` into the workspace (diffqkv_augment_q_workspace_bytes: M x inter elements).
+ * Returns a diffqkv_status; on error nothing is enqueued.
+ */
+typedef struct diffqkv_augq_shape {
+  int32_t M;      /* tokens */
+  int32_t hidden; /* width of q_in and q_out */
+  int32_t inter;  /* intermediate width */
+  int32_t dtype;  /* DIFFQKV_F32 or DIFFQKV_BF16 */
+} diffqkv_augq_shape;
+size_t diffqkv_augment_q_workspace_bytes(const diffqkv_augq_shape* shape /* host */);
+int diffqkv_augment_q(const diffqkv_augq_shape* shape /* host */, const void* q_in, const void* w_gate,
+                      const void* w_up, const void* w_down, void* q_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement aid: reads `bytes` (a multiple of 16) from `src` with 128-bit loads, as fast as the
  * memory system allows, and writes one float per workgroup to `sink` (at least 4096 floats) so the
  * reads cannot be elided.  Used to measure the achievable HBM read rate beside the decode kernels.

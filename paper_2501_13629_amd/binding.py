@@ -24,6 +24,7 @@ EXPORTS = (
     "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_probe_stream_read", "diffqkv_strerror",
     "diffqkv_version", "diffqkv_set_split_event", "diffqkv_append", "diffqkv_append_paged",
     "diffqkv_decode_topk_workspace_bytes", "diffqkv_decode_topk", "diffqkv_decode_topk_paged",
+    "diffqkv_augment_q_workspace_bytes", "diffqkv_augment_q",
 )
 
 
@@ -31,6 +32,10 @@ class Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "n_q", "n_k", "n_v", "d_qk", "d_v", "dtype")] + [
         ("softmax_scale", ctypes.c_float)
     ]
+
+
+class AugqShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("M", "hidden", "inter", "dtype")]
 
 
 class Tuning(ctypes.Structure):
@@ -86,6 +91,10 @@ def load_library() -> ctypes.CDLL:
     lib.diffqkv_append.argtypes = [sp, vp, vp, vp, vp] + [i64] * 6 + [vp, i32, vp, vp]
     lib.diffqkv_append_paged.restype = ctypes.c_int
     lib.diffqkv_append_paged.argtypes = [sp, vp, vp, vp, vp] + [i64] * 6 + [vp, i32, i32, vp, vp, vp]
+    lib.diffqkv_augment_q_workspace_bytes.restype = sz
+    lib.diffqkv_augment_q_workspace_bytes.argtypes = [ctypes.POINTER(AugqShape)]
+    lib.diffqkv_augment_q.restype = ctypes.c_int
+    lib.diffqkv_augment_q.argtypes = [ctypes.POINTER(AugqShape), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.diffqkv_probe_stream_read.restype = ctypes.c_int
     lib.diffqkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.diffqkv_strerror.restype = ctypes.c_char_p
@@ -376,3 +385,30 @@ def diffqkv_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor):
     nbytes = buf.numel() * buf.element_size()
     assert sink.dtype == torch.float32 and sink.numel() >= 4096
     _check(load_library().diffqkv_probe_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream(buf)))
+
+
+def diffqkv_augment_q(q_in, w_gate, w_up, w_down, out=None, workspace=None):
+    """Augmented Q: q_in [M, hidden] -> W_down(silu(W_gate q_in) * (W_up q_in)) [M, hidden].
+    w_gate, w_up [inter, hidden]; w_down [hidden, inter]; all contiguous, one dtype."""
+    _dev(q_in, w_gate, w_up, w_down, out, workspace)
+    dt = _dtype_code(q_in)
+    if any(_dtype_code(w) != dt for w in (w_gate, w_up, w_down)):
+        raise TypeError("q_in and the weights must share a dtype")
+    if not all(t.is_contiguous() for t in (q_in, w_gate, w_up, w_down)):
+        raise ValueError("q_in and the weights must be contiguous")
+    M, hidden = q_in.shape
+    inter = w_gate.shape[0]
+    if tuple(w_gate.shape) != (inter, hidden) or tuple(w_up.shape) != (inter, hidden) or \
+            tuple(w_down.shape) != (hidden, inter):
+        raise ValueError("weight shapes do not match q_in")
+    if out is None:
+        out = torch.empty_like(q_in)
+    elif tuple(out.shape) != (M, hidden) or out.dtype != q_in.dtype or not out.is_contiguous():
+        raise ValueError("out must be a contiguous [M, hidden] tensor of the input dtype")
+    lib = load_library()
+    s = AugqShape(int(M), int(hidden), int(inter), dt)
+    need = int(lib.diffqkv_augment_q_workspace_bytes(ctypes.byref(s)))
+    ws = _workspace(need, q_in, workspace)
+    _check(lib.diffqkv_augment_q(ctypes.byref(s), _ptr(q_in), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out),
+                                 _ptr(ws), ws.numel() * ws.element_size(), _stream(q_in)))
+    return out

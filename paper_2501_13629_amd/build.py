@@ -17,7 +17,7 @@ INCLUDE = PKG.parent / "include"
 LIB = PKG / "libdiffqkv.so"
 OBJ = PKG / "_build"
 
-SOURCES = ["api.hip", "decode_generic.hip", "decode_mfma.hip", "prefill_generic.hip", "prefill_mfma.hip", "prefill_mfma64.hip", "probe.hip", "append.hip", "topk.hip"]
+SOURCES = ["api.hip", "decode_generic.hip", "decode_mfma.hip", "prefill_generic.hip", "prefill_mfma.hip", "prefill_mfma64.hip", "probe.hip", "append.hip", "topk.hip", "augq.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -482,6 +482,52 @@ int diffqkv_prefill(const diffqkv_shape* shape, const void* q, const void* k, co
   return e == hipSuccess ? DIFFQKV_OK : DIFFQKV_ERR_HIP;
 }
 
+static int check_augq(const diffqkv_augq_shape* s) {
+  if (!s) return DIFFQKV_ERR_NULL;
+  if (s->M < 0 || s->hidden <= 0 || s->inter <= 0 || s->hidden % 8 || s->inter % 8) return DIFFQKV_ERR_SHAPE;
+  if (s->dtype != DIFFQKV_F32 && s->dtype != DIFFQKV_BF16) return DIFFQKV_ERR_SHAPE;
+  if ((int64_t)s->hidden * s->inter > (1ll << 40) || (int64_t)s->M * s->inter > (1ll << 40)) return DIFFQKV_ERR_SHAPE;
+  return DIFFQKV_OK;
+}
+
+size_t diffqkv_augment_q_workspace_bytes(const diffqkv_augq_shape* shape) {
+  if (check_augq(shape) != DIFFQKV_OK) return 0;
+  const size_t elem = shape->dtype == DIFFQKV_F32 ? 4 : 2;
+  return ((size_t)shape->M * shape->inter * elem + 255) / 256 * 256;
+}
+
+int diffqkv_augment_q(const diffqkv_augq_shape* shape, const void* q_in, const void* w_gate, const void* w_up,
+                      const void* w_down, void* q_out, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  int rc = check_augq(shape);
+  if (rc != DIFFQKV_OK) return rc;
+  if (shape->M == 0) return DIFFQKV_OK;
+  if (!q_in || !w_gate || !w_up || !w_down || !q_out) return DIFFQKV_ERR_NULL;
+  if (!aligned16(q_in) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(q_out))
+    return DIFFQKV_ERR_ALIGN;
+  const size_t need = diffqkv_augment_q_workspace_bytes(shape);
+  if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return DIFFQKV_ERR_ALIGN;
+  const bool mfma = !g_tuning.force_generic && augq_mfma_supported(shape->dtype, shape->hidden, shape->inter);
+  AugqParams p = {};
+  p.x = q_in;
+  p.w0 = w_gate;
+  p.w1 = w_up;
+  p.out = workspace;
+  p.M = shape->M;
+  p.K = shape->hidden;
+  p.N = shape->inter;
+  if (launch_augq(p, shape->dtype, true, mfma, (hipStream_t)hip_stream) != hipSuccess) return DIFFQKV_ERR_HIP;
+  p.x = workspace;
+  p.w0 = w_down;
+  p.w1 = nullptr;
+  p.out = q_out;
+  p.K = shape->inter;
+  p.N = shape->hidden;
+  return launch_augq(p, shape->dtype, false, mfma, (hipStream_t)hip_stream) == hipSuccess ? DIFFQKV_OK
+                                                                                           : DIFFQKV_ERR_HIP;
+}
+
 int diffqkv_probe_stream_read(const void* src, size_t bytes, float* sink, void* hip_stream) {
   if (!src || !sink) return DIFFQKV_ERR_NULL;
   if (bytes % 16 || !aligned16(src)) return DIFFQKV_ERR_ALIGN;

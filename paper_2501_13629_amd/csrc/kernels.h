@@ -97,6 +97,18 @@ int topk_max_k();
 bool topk_scores_mfma_supported(const TopkParams& p, int dtype);
 hipError_t launch_topk(const TopkParams& p, int dtype, bool paged, bool mfma, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, bool paged, hipStream_t s);
+
+// One product of the augmented-Q feed-forward: out[M, N] = W0 x, or silu(W0 x) * (W1 x) when gated;
+// x [M, K], W0 / W1 [N, K] row-major, everything in the I/O dtype.
+struct AugqParams {
+  const void* x;
+  const void* w0;
+  const void* w1;  // gated only
+  void* out;
+  int32_t M, K, N;
+};
+bool augq_mfma_supported(int dtype, int hidden, int inter);
+hipError_t launch_augq(const AugqParams& p, int dtype, bool gated, bool mfma, hipStream_t s);
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------------------------

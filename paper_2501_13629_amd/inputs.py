@@ -157,6 +157,20 @@ def make_prefill(cfg) -> dict:
     return dict(q=q, k=k, v=v, S_q=S, S_k=S_k)
 
 
+def make_augq(M: int, hidden: int, inter: int, dtype: str = "bf16", index: int = 40) -> dict:
+    """Augmented-Q inputs: q_in [M, hidden] ~ N(0,1); weights of linear layers [out, in] ~ N(0, 1/in)
+    (so that every product keeps unit scale), w_gate and w_up [inter, hidden], w_down [hidden, inter].
+    Sigma's widths are hidden 2048 / inter 3072 and 4096 / 6144 (section 3.1 and its model table)."""
+    dt = torch.float32 if dtype == "f32" else torch.bfloat16
+    seed = BASE_SEED + index
+    return dict(
+        q_in=normal_tensor((M, hidden), seed, 0, dt),
+        w_gate=normal_tensor((inter, hidden), seed, 1, dt, row_scale=torch.full((hidden,), hidden ** -0.5)),
+        w_up=normal_tensor((inter, hidden), seed, 2, dt, row_scale=torch.full((hidden,), hidden ** -0.5)),
+        w_down=normal_tensor((hidden, inter), seed, 3, dt, row_scale=torch.full((inter,), inter ** -0.5)),
+    )
+
+
 def as_numpy(t: torch.Tensor) -> np.ndarray:
     """Host view for the CPU oracle: fp32 stays float32, bf16 becomes its uint16 bit patterns
     (no value changes; strides preserved)."""

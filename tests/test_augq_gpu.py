@@ -1,0 +1,58 @@
+"""GPU parity: the augmented-Q gated feed-forward against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import util
+from paper_2501_13629_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_tuning():
+    binding.diffqkv_set_tuning()
+    yield
+    binding.diffqkv_set_tuning()
+
+
+def run(M, hidden, inter, dtype, index, force_generic=False):
+    d = inputs.make_augq(M, hidden, inter, dtype, index)
+    binding.diffqkv_set_tuning(force_generic=force_generic)
+    out = binding.diffqkv_augment_q(*(util.dev(d[k]) for k in ("q_in", "w_gate", "w_up", "w_down")))
+    torch.cuda.synchronize()
+    ref = oracle.augment_q(*(inputs.as_numpy(d[k]) for k in ("q_in", "w_gate", "w_up", "w_down")))
+    # outputs have unit scale; bf16: the output rounding (2^-9 relative) and the once-rounded
+    # intermediate activations stay well inside the 2e-2 bound; fp32: accumulation order only
+    return util.check(out, ref, dtype, "M=%d hidden=%d inter=%d" % (M, hidden, inter))
+
+
+@pytest.mark.parametrize("M", [1, 8, 16, 17, 40])
+def test_sigma_1p5b_widths_matrix_cores(M):
+    run(M, 2048, 3072, "bf16", 41)
+
+
+def test_sigma_10b_widths_matrix_cores():
+    run(8, 4096, 6144, "bf16", 42)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(1, 8, 8), (3, 64, 96), (5, 200, 312), (2, 1024, 1032), (20, 256, 384)])
+def test_portable_kernel_any_width(dtype, shape):
+    run(*shape, dtype, 43)
+
+
+def test_portable_kernel_agrees_on_matrix_core_shapes():
+    run(4, 1024, 2048, "bf16", 44, force_generic=True)
+    run(4, 1024, 2048, "bf16", 44)
+
+
+def test_empty_batch_and_bad_arguments():
+    d = inputs.make_augq(2, 64, 96, "bf16", 45)
+    a = [util.dev(d[k]) for k in ("q_in", "w_gate", "w_up", "w_down")]
+    assert tuple(binding.diffqkv_augment_q(a[0][:0], *a[1:]).shape) == (0, 64)
+    with pytest.raises(ValueError):
+        binding.diffqkv_augment_q(a[0], a[1], a[2][:, :32].contiguous(), a[3])
+    with pytest.raises(binding.DiffQKVError):
+        binding.diffqkv_augment_q(a[0], a[1], a[2], a[3], workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
