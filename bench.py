@@ -34,7 +34,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="decode_32k",
-                    choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k"])
+                    choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k", "augq_1p5b", "augq_10b"],
+                    help="the last two time the augmented-Q feed-forward of a decode step (16 tokens) at "
+                         "Sigma-1.5B / Sigma-10B widths: weight bytes per second")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--top-k", type=int, default=-1,
                     help="contiguous decode workloads only: selective V-cache fetching with this top_k "
@@ -60,6 +62,8 @@ def main():
     binding.load_library()  # fail loudly if the HIP library is not built
     binding.diffqkv_set_tuning(decode_chunk_tokens=args.chunk, prefill_waves=args.prefill_waves)
     dev = torch.device("cuda:0")
+    if args.workload.startswith("augq"):
+        return bench_augq(args, torch, binding, inputs, dev)
     cfg = inputs.config(args.workload)
     kind = cfg["kind"]
     topk = args.top_k
@@ -216,6 +220,68 @@ def main():
         "roofline": roof, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def bench_augq(args, torch, binding, inputs, dev):
+    """The augmented-Q feed-forward of one decode step: 16 tokens, weights streamed once per step."""
+    M = 16
+    hidden, inter = (2048, 3072) if args.workload == "augq_1p5b" else (4096, 6144)
+    host = inputs.make_augq(M, hidden, inter, "bf16", 46)
+    names = ("q_in", "w_gate", "w_up", "w_down")
+    wbytes = 3 * hidden * inter * 2
+    n_sets = max(2, min(16, int(-(-ROTATE_BYTES // wbytes))))  # distinct weight copies: no cache reuse across steps
+    sets = [[host[n].to(dev) for n in names]]
+    for _ in range(n_sets - 1):
+        sets.append([sets[0][0]] + [t.clone() for t in sets[0][1:]])
+    out = torch.empty((M, hidden), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(M * inter * 2 + 256, dtype=torch.uint8, device=dev)
+
+    def step(i):
+        binding.diffqkv_augment_q(*sets[i % n_sets], out=out, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us = wall * 1e6 / args.steps
+    n_ev = min(args.steps, 100)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        step(i)
+        b.record()
+    torch.cuda.synchronize()
+    ev_us = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    avg = sum(ev_us) / len(ev_us)
+    value = wbytes / (us * 1e-6) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        a = [inputs.as_numpy(host[n]) for n in names]
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            oracle.augment_q(*a)
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= 10.0 or reps >= 1000:
+                break
+        cpu = {"value": round(wbytes * reps / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "the full workload, %d evaluations" % reps, "seconds": round(dt, 3)}
+    print(json.dumps({
+        "metric": "augmented-Q feed-forward, weight GB/s", "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "us_per_step": round(us, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "hidden": hidden, "inter": inter, "weight_bytes_per_step": wbytes,
+                   "weight_sets_in_rotation": n_sets},
+        "roofline": {"bound": "hbm", "achieved": round(wbytes / (avg * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(wbytes / (avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "augq_mfma_kernel<true> + <false> (both launches)", "kernel_avg_us": round(avg, 2),
+                     "kernel_min_us": round(ev_us[0], 2), "algorithmic_bytes_per_launch": wbytes},
+        "cpu_baseline": cpu}))
 
 
 def cpu_baseline(cfg, host, kind, kv_bytes, topk=-1):

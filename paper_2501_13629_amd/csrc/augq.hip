@@ -7,9 +7,9 @@
 //
 // Matrix-core kernel: D^T[feature][token] = W x^T on v_mfma_f32_16x16x32_bf16 with the weight rows
 // loaded from HBM straight into A-operand layout (each lane 16 contiguous bytes of one row) and up to
-// 16 tokens of x as the B operand.  One workgroup = 8 wavefronts owns 16 output features (of both
-// gate and up in the gated pass); the wavefronts split the input features eight ways, so every
-// weight byte is read once and ~190 workgroups x 8 wavefronts have all their loads in flight at
+// 16 tokens of x as the B operand.  One workgroup = 16 wavefronts owns 16 output features (of both
+// gate and up in the gated pass); the wavefronts split the input features sixteen ways, so every
+// weight byte is read once and ~190 workgroups x 16 wavefronts have their loads in flight at
 // once; partial sums meet in LDS, where the activation and the product are applied.  Two launches:
 // gate + up -> intermediate (I/O dtype) in the workspace, then down.  More than 16 tokens repeat the
 // pass per block of 16 (weights then come from L2): the entry point is meant for the decode step.
@@ -24,12 +24,11 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kWavesMfma = 8;
-constexpr int kBatch = 4;  // k-steps (32 input features each) loaded together per wavefront
+constexpr int kWavesMfma = 16;  // the k-steps (32 input features each) of a wavefront are loaded in batches of 4 or 6
 
 __device__ __forceinline__ float silu(float z) { return z / (1.f + __expf(-z)); }
 
-template <bool GATED>
+template <bool GATED, int kBatch>
 __global__ __launch_bounds__(kWavesMfma * 64) void augq_mfma_kernel(AugqParams p) {
   __shared__ float red[kWavesMfma][GATED ? 2 : 1][16][16];  // [wavefront][matrix][token][feature]
   const int tile = blockIdx.x, tb = blockIdx.y;
@@ -103,9 +102,16 @@ __global__ __launch_bounds__(256) void augq_generic_kernel(AugqParams p) {
 
 }  // namespace
 
-bool augq_mfma_supported(int dtype, int hidden, int inter) {
-  const int q = kWavesMfma * 32 * kBatch;  // input features per pass of the workgroup
-  return dtype == 1 && hidden % q == 0 && inter % q == 0;  // (multiples of 1024: also multiples of 16)
+namespace {
+int batch_for(int K) {  // k-steps per wavefront must come in whole batches
+  if (K % (kWavesMfma * 32)) return 0;
+  const int ksteps = K / (kWavesMfma * 32);
+  return ksteps % 6 == 0 ? 6 : ksteps % 4 == 0 ? 4 : 0;
+}
+}  // namespace
+
+bool augq_mfma_supported(int dtype, int hidden, int inter) {  // multiples of 2048 or 3072
+  return dtype == 1 && batch_for(hidden) && batch_for(inter);
 }
 
 // One product: out[M, N] = act(W0 x)(* W1 x), x [M, K], W [N, K].
@@ -113,8 +119,14 @@ hipError_t launch_augq(const AugqParams& p, int dtype, bool gated, bool mfma, hi
   if (p.M == 0) return hipSuccess;
   if (mfma) {
     dim3 grid(p.N / 16, (p.M + 15) / 16);
-    if (gated) augq_mfma_kernel<true><<<grid, kWavesMfma * 64, 0, s>>>(p);
-    else augq_mfma_kernel<false><<<grid, kWavesMfma * 64, 0, s>>>(p);
+    const bool six = batch_for(p.K) == 6;
+    if (gated) {
+      if (six) augq_mfma_kernel<true, 6><<<grid, kWavesMfma * 64, 0, s>>>(p);
+      else augq_mfma_kernel<true, 4><<<grid, kWavesMfma * 64, 0, s>>>(p);
+    } else {
+      if (six) augq_mfma_kernel<false, 6><<<grid, kWavesMfma * 64, 0, s>>>(p);
+      else augq_mfma_kernel<false, 4><<<grid, kWavesMfma * 64, 0, s>>>(p);
+    }
   } else {
     dim3 grid((p.N + 3) / 4, p.M);
     if (dtype == 0) {

@@ -44,8 +44,8 @@ def test_portable_kernel_any_width(dtype, shape):
 
 
 def test_portable_kernel_agrees_on_matrix_core_shapes():
-    run(4, 1024, 2048, "bf16", 44, force_generic=True)
-    run(4, 1024, 2048, "bf16", 44)
+    run(4, 2048, 6144, "bf16", 44, force_generic=True)
+    run(4, 2048, 6144, "bf16", 44)
 
 
 def test_empty_batch_and_bad_arguments():
