@@ -1,4 +1,4 @@
-// Causal prefill for bf16 on gfx950 matrix cores.
+// Causal prefill for bf16 on gfx950 matrix cores, 32 query rows per wavefront.
 //
 // The same attention as decode (section 2, "Formulation of DiffQKV Attention"), for a block of S_q
 // query positions: query i attends to keys j <= i + (S_k - S_q) (K_t holds the tokens up to the
@@ -6,18 +6,20 @@
 // "idx" rule of section 3.2).  Prefill is a dense contraction, so both products run on
 // v_mfma_f32_32x32x16_bf16.
 //
-// One workgroup = 4 wavefronts = 128 query rows of one (sequence, query head); each wavefront owns
-// 32 rows.  K/V tiles of 64 tokens are staged through LDS, double-buffered: the global loads of
-// tile i+1 are in flight while tile i is in the matrix cores.
+// One workgroup = 8 (or 4) wavefronts = 256 (128) query rows of one (sequence, query head); each
+// wavefront owns 32 rows, two wavefronts share a SIMD.  K/V tiles of 64 tokens are staged through LDS,
+// double-buffered: the global loads of tile i+1 are in flight while tile i is in the matrix cores.
 //   S^T = K Q^T    A = K tile from LDS (row-major, padded rows), B = Q^T held in registers.
 //                  In the result each lane column is one query row, so the online-softmax state
-//                  and the accumulator rescale are lane-local (one cross-lane exchange per tile).
+//                  and the accumulator rescale are lane-local.
 //   O^T = V^T P^T  B = P^T is the softmax output exactly as it sits in registers; A = V^T is read
 //                  from an LDS copy of the tile that was transposed on the way in (each thread
 //                  loads 4 tokens x 8 channels and transposes them in registers), stored with the
 //                  token order that the score layout produces.
 // Workgroups are ordered so that the query heads sharing a K head run side by side on one XCD
 // (its L2 then serves their common K/V tiles), heaviest query tiles first.
+// This kernel serves the head widths (64, 64), (64, 128) and, on request, (128, 128); for (128, 128)
+// the 64-rows-per-wavefront kernel of prefill_mfma64.hip is the default.
 #include "prefill_tile.h"
 
 namespace diffqkv {
@@ -26,11 +28,10 @@ namespace {
 
 using namespace prefill_tile;
 
-// NW wavefronts (4 or 8) of QB x 32 query rows each per workgroup.  With 8 wavefronts the K/V tile is
-// staged once for 256 query rows, and half of the wavefronts stage K while the other half transpose
-// V.  With QB = 2 (4 wavefronts, one per SIMD, the whole register file each: accumulators in the
-// accumulation registers) every K and V^T fragment read from LDS feeds two matrix instructions, which
-// halves the LDS traffic per flop.
+// NW wavefronts (4 or 8) of QB x 32 query rows each per workgroup (QB = 1 in every instantiation; two
+// row blocks per wavefront need the whole register file and have a kernel of their own).  With 8
+// wavefronts the K/V tile is staged once for 256 query rows, and half of the wavefronts stage K
+// while the other half transpose V.
 template <int DQK, int DV, int NW, int QB>
 __global__ __launch_bounds__(NW * 64, QB == 2 ? 1 : 2) void prefill_mfma_kernel(PrefillParams p, int n_qtiles,
                                                                                int xcd_aware) {

@@ -108,6 +108,47 @@ def test_paged_and_prefill_validation_codes(lib):
     assert prefill(q=0x1008) == E_ALIGN
 
 
+def test_topk_and_augmented_q_validation_codes(lib):
+    vp = ctypes.c_void_p
+    s = shape()
+
+    def topk(top_k=100, T=64, q=0x1000, ws=0x5000, ws_bytes=1 << 30, kst=(8192, 4096, 64)):
+        return lib.diffqkv_decode_topk(ctypes.byref(s), vp(q), vp(0x2000), vp(0x3000), *kst, 8192, 4096, 64, None, T,
+                                       top_k, 0, vp(0x4000), None, None, vp(ws), ws_bytes, None)
+
+    assert topk(top_k=-1) == E_SHAPE
+    assert topk(top_k=513) == E_SHAPE  # more than the select kernel keeps in LDS
+    assert topk(T=-1) == E_SHAPE
+    assert topk(q=0) == E_NULL
+    assert topk(q=0x1004) == E_ALIGN
+    assert topk(kst=(8192, 4096, 32)) == E_SHAPE
+    assert topk(ws=0) == E_WS
+    assert topk(ws_bytes=64) == E_WS
+    need = lib.diffqkv_decode_topk_workspace_bytes(ctypes.byref(s), 1000)
+    assert need == 2 * 8 * 1024 * 4  # one fp32 score row per (sequence, query head), padded to 128 tokens
+
+    A = binding.AugqShape
+
+    def augq(a, q=0x1000, wd=0x4000, ws=0x6000, ws_bytes=1 << 30):
+        return lib.diffqkv_augment_q(ctypes.byref(a), vp(q), vp(0x2000), vp(0x3000), vp(wd), vp(0x5000), vp(ws),
+                                     ws_bytes, None)
+
+    assert lib.diffqkv_augment_q(None, vp(16), vp(16), vp(16), vp(16), vp(16), vp(16), 0, None) == E_NULL
+    assert augq(A(-1, 64, 96, 1)) == E_SHAPE
+    assert augq(A(4, 0, 96, 1)) == E_SHAPE
+    assert augq(A(4, 60, 96, 1)) == E_SHAPE  # rows must be whole 16-byte pieces
+    assert augq(A(4, 64, 96, 5)) == E_SHAPE
+    assert augq(A(4, 64, 96, 1), q=0) == E_NULL
+    assert augq(A(4, 64, 96, 1), wd=0x4008) == E_ALIGN
+    assert augq(A(4, 64, 96, 1), ws=0) == E_WS
+    assert augq(A(4, 64, 96, 1), ws_bytes=100) == E_WS
+    assert augq(A(0, 64, 96, 1), q=0, ws=0, ws_bytes=0) == OK  # no tokens: a valid no-op
+    a = A(16, 2048, 3072, 1)
+    assert lib.diffqkv_augment_q_workspace_bytes(ctypes.byref(a)) == 16 * 3072 * 2
+    a = A(3, 64, 96, 0)
+    assert lib.diffqkv_augment_q_workspace_bytes(ctypes.byref(a)) == 1280  # 3 x 96 x 4 = 1152, rounded up to 256
+
+
 def test_split_plan_is_a_function_of_shapes(lib):
     s = shape(B=8, n_q=32, n_k=2, n_v=8, d_qk=128, d_v=128)
     a = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
