@@ -200,12 +200,24 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));  // Q has arrived, and sits in accumulation registers
   __syncthreads();
 
+  // Softmax without a running maximum on the hot path.  Scores stay unscaled; the scale (> 0) is
+  // folded into the exponent: p = 2^(c s - m_ref).  The reference m_ref of a row only has to keep the
+  // exponentials in range; it need not track the maximum.  So the weights of a block are computed
+  // against the reference as it stands, their sum is kept apart (l_blk), and once the block is complete
+  // -- before its output product starts -- one comparison per lane checks that no sum has left the
+  // range [0, kBig].  Only then (the first block of a wavefront, where m_ref is still the initial
+  // -1e30, and later if a score exceeds the reference by more than ~36 in log2 units) the block maximum
+  // is taken, the reference raised, accumulators and row sums rescaled and the block's weights
+  // computed again.  Weights stay below 2^40, inside bf16 / fp32 range with room for the sums; the final
+  // division by the row sum removes the reference.
+  constexpr float kBig = 1.0995116e12f;  // 2^40
+  float l_blk[2][2] = {{0.f, 0.f}, {0.f, 0.f}};  // [token block][row block]: sum of the block's weights
   // two of a row block's 16 weights of a token block
   auto weights_piece = [&](int blk, int qb, int i) {
     const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i], p.scale_log2, -m_run[qb]));
     const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][blk][2 * i + 1], p.scale_log2, -m_run[qb]));
     pw[qb][blk][i] = pack_bf16x2(p0, p1);
-    l_run[qb] += p0 + p1;
+    l_blk[blk][qb] += p0 + p1;
   };
   // The same in two halves, numbered h = 0..31 per token block: groups of eight halves cover pieces
   // 0-3 of row block 0, 0-3 of row block 1, 4-7 of row block 0, 4-7 of row block 1; an even half
@@ -221,18 +233,43 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       asm volatile("" : "+v"(tp[0]), "+v"(tp[1]));
     } else {
       pw[qb][blk][i] = pack_bf16x2(tp[0], tp[1]);
-      l_run[qb] += tp[0] + tp[1];
-      asm volatile("" : "+v"(pw[qb][blk][i]), "+v"(l_run[qb]));
+      l_blk[blk][qb] += tp[0] + tp[1];
+      asm volatile("" : "+v"(pw[qb][blk][i]), "+v"(l_blk[blk][qb]));
     }
   };
-  auto rescale = [&](const float (&fac)[2]) {
-    if (__builtin_amdgcn_ballot_w64(fac[0] != 1.f || fac[1] != 1.f)) {
+  // The block is complete: range check, then its sums join the row sums.
+  auto close_block = [&](auto blkc) {
+    constexpr int blk = decltype(blkc)::value;
+    const float worst = fmaxf(l_blk[blk][0], l_blk[blk][1]);
+    if (__builtin_amdgcn_ballot_w64(!(worst <= kBig))) {  // (a NaN also lands here, and stays a NaN)
       settle_a<CB>(acc);
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int qb = 0; qb < 2; ++qb) {
+        float m_blk = -INFINITY;
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) acc[qb][cb] *= fac[qb];
+        for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, s[qb][blk][r]);
+        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));  // the lane holding the row's other 16 tokens
+        const float m_new = fmaxf(m_run[qb], m_blk * p.scale_log2);
+        const float fac = __builtin_amdgcn_exp2f(m_run[qb] - m_new);  // from the initial reference: 0
+        m_run[qb] = m_new;
+        l_run[qb] *= fac;
+        // (one accumulator tile at a time: this rare path must not raise the register demand of the
+        //  whole kernel, or the allocator spills hot-loop values to make room for it)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          acc[qb][cb] *= fac;
+          asm volatile("" : "+a"(acc[qb][cb]));
+        }
+        l_blk[blk][qb] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) weights_piece(blk, qb, i);
+      }
       settle_a<CB>(acc);
+    }
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      l_run[qb] += l_blk[blk][qb];
+      l_blk[blk][qb] = 0.f;
     }
   };
   // V^T fragment of 16-token step kq, channel block cb, from tile buffer vb
@@ -274,8 +311,6 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       };
       static_for<0, kRing>(fetch);
       __builtin_amdgcn_sched_barrier(0);
-      float fac0[2], fac1[2];
-      float mb[2];  // block maximum of the reference in progress
       float tp[2];  // exponentials waiting to be packed by the next half
 
       // A wavefront issues in order; the matrix pipe takes one instruction per 32 cycles and holds
@@ -290,40 +325,20 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       //   step (28 slots: the first four take two halves each); row block 0 / 1 alternate in groups
       //   of four pieces so that everything is ready when the output product asks for it;
       //   staging (LDS stores of the next tile, then the loads of the one after) on odd slots.
-      // Softmax reference: register r of a score tile is token t0 + 32 blk + 8 (r/4) + 4 half + r%4.
-      // Scores stay unscaled; the scale (> 0) is folded into the exponent: 2^(c s - m_ref).  The
-      // reference is raised (and the accumulators rescaled) only when some row's block maximum
-      // exceeds it by more than kSlack; each lane first tests its own 16 tokens and the exchange
-      // with the lane holding the row's other 16 happens only then.
-      auto reference_chunk = [&](auto blkc, auto cc, float (&fac)[2]) {
-        constexpr int blk = decltype(blkc)::value, c = decltype(cc)::value;
-        constexpr int qb = c / 2, part = c % 2;
-        if constexpr (c == 0) settle_v(s[0][blk], s[1][blk]);
-        const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
-        float m_blk = part == 0 ? -INFINITY : mb[qb];
+      // Register r of a score tile is token t0 + 32 blk + 8 (r/4) + 4 half + r%4.  On and past the
+      // diagonal the scores of tokens a row may not see are replaced by -inf as soon as the block's
+      // score product is complete (weight 0, and no part in a block maximum).
+      auto mask_block = [&](auto blkc) {
+        constexpr int blk = decltype(blkc)::value;
+        settle_v(s[0][blk], s[1][blk]);
 #pragma unroll
-        for (int r = part * 8; r < (part + 1) * 8; ++r) {
-          float v = s[qb][blk][r];
-          if (MASKED) {
+        for (int qb = 0; qb < 2; ++qb) {
+          const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
             const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
-            v = (tok <= row_limit && tok < p.S_k) ? v : -INFINITY;
-            s[qb][blk][r] = v;
+            s[qb][blk][r] = (tok <= row_limit && tok < p.S_k) ? s[qb][blk][r] : -INFINITY;
           }
-          m_blk = fmaxf(m_blk, v);
-        }
-        mb[qb] = m_blk;
-        if constexpr (part == 1) {
-          fac[qb] = 1.f;
-          if (__builtin_amdgcn_ballot_w64(m_blk * p.scale_log2 > m_run[qb] + kSlack)) {
-            m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
-            const float m_cand = m_blk * p.scale_log2;
-            const float m_new = (m_cand > m_run[qb] + kSlack) ? m_cand : m_run[qb];
-            fac[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            l_run[qb] *= fac[qb];
-          }
-        } else {
-          asm volatile("" : "+v"(mb[qb]));  // pinned to its slot
         }
       };
       auto stage_item = [&](auto ic) {
@@ -337,8 +352,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       };
       auto slot = [&](auto gc) {
         constexpr int g = decltype(gc)::value;
-        if constexpr (g >= 16 && g < 20) reference_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, g - 16>{}, fac0);
-        if constexpr (g >= 48 && g < 52) reference_chunk(std::integral_constant<int, 1>{}, std::integral_constant<int, g - 48>{}, fac1);
+        if constexpr (MASKED && g == 16) mask_block(std::integral_constant<int, 0>{});
+        if constexpr (MASKED && g == 48) mask_block(std::integral_constant<int, 1>{});
         if constexpr (g >= 20 && g < 24) {
           weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * (g - 20)>{}, tp);
           weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * (g - 20) + 1>{}, tp);
@@ -350,6 +365,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         }
         if constexpr (g >= 56) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 8 + g - 56>{}, tp);
         if constexpr (g < 16) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 16 + g>{}, tp);
+        if constexpr (g == 15) close_block(std::integral_constant<int, 1>{});  // the previous tile's second block
+        if constexpr (g == 47) close_block(std::integral_constant<int, 0>{});
         if constexpr ((g & 1) && g < 16) stage_item(std::integral_constant<int, g / 2>{});
         if constexpr ((g & 1) && g >= 25 && g < 25 + 2 * (KLD + 10 - 8)) stage_item(std::integral_constant<int, 8 + (g - 25) / 2>{});
       };
@@ -377,9 +394,6 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (f + kRing < kFrags) fetch(std::integral_constant<int, f + kRing>{});
         slot(std::integral_constant<int, 2 * f + 1>{});
-        // accumulators gathered under the old reference are rescaled once their phase is complete
-        if constexpr (f == G1 - 1) rescale(fac0);
-        if constexpr (f == kFrags - 1) rescale(fac1);
         __builtin_amdgcn_sched_barrier(0);
       });
       pending = true;
@@ -397,6 +411,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
       for (int i = 4; i < 8; ++i) weights_piece(1, qb, i);  // the halves the next step would have taken
+    close_block(std::integral_constant<int, 1>{});
 #pragma unroll
     for (int j = 0; j < 2 * CB; ++j) {
       const u32x4 a = vt_frag(vprev, 2 + j / CB, j % CB);
