@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   constexpr int KLD = kBN * (DQK / 8) / kThreads;
   constexpr int kChunkBits = (DV == 128) ? 4 : 3;
   constexpr int kVItems = 16 * (DV / 8);
-  const bool v_role = wave < kVItems / 64;  // whole wavefronts
+  const bool v_role = kVItems >= kThreads || wave < kVItems / 64;  // whole wavefronts; all of them at d_v = 128
   const int v_c8 = (tid & 7) | ((kChunkBits == 4) ? ((tid >> 1) & 8) : 0);
   const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
   const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
@@ -318,12 +318,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       // back, or a long run of vector work, both leave one of the pipes idle.  Every matrix
       // instruction is therefore followed by a "slot" with an even share of all the other work of
       // the step.  Slots are numbered g = 0..63 (phase p covers 16 p .. 16 p + 15):
-      //   reference of block 0 in four chunks at g = 16..19, of block 1 at g = 48..51 (the matrix
-      //   instructions of phases 2 and 4 do not depend on them);
       //   the weights of a token block as 32 half-pieces -- even: two exponentials, odd: pack and sum
-      //   -- for block 0 at g = 20..47, for block 1 at g = 52..63 and on into g = 0..15 of the next
-      //   step (28 slots: the first four take two halves each); row block 0 / 1 alternate in groups
-      //   of four pieces so that everything is ready when the output product asks for it;
+      //   -- one per slot: block 0 at g = 16..47 (its scores are complete after phase 1, its output
+      //   product starts with phase 4), block 1 at g = 48..63 and on into g = 0..15 of the next step;
+      //   row block 0 / 1 alternate in groups of four pieces so that everything is ready when the
+      //   output product asks for it; the range check that closes a block follows its last half;
       //   staging (LDS stores of the next tile, then the loads of the one after) on odd slots.
       // Register r of a score tile is token t0 + 32 blk + 8 (r/4) + 4 half + r%4.  On and past the
       // diagonal the scores of tokens a row may not see are replaced by -inf as soon as the block's
@@ -354,16 +353,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         constexpr int g = decltype(gc)::value;
         if constexpr (MASKED && g == 16) mask_block(std::integral_constant<int, 0>{});
         if constexpr (MASKED && g == 48) mask_block(std::integral_constant<int, 1>{});
-        if constexpr (g >= 20 && g < 24) {
-          weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * (g - 20)>{}, tp);
-          weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * (g - 20) + 1>{}, tp);
-        }
-        if constexpr (g >= 24 && g < 48) weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 8 + g - 24>{}, tp);
-        if constexpr (g >= 52 && g < 56) {
-          weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (g - 52)>{}, tp);
-          weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 2 * (g - 52) + 1>{}, tp);
-        }
-        if constexpr (g >= 56) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 8 + g - 56>{}, tp);
+        if constexpr (g >= 16 && g < 48) weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, g - 16>{}, tp);
+        if constexpr (g >= 48) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, g - 48>{}, tp);
         if constexpr (g < 16) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 16 + g>{}, tp);
         if constexpr (g == 15) close_block(std::integral_constant<int, 1>{});  // the previous tile's second block
         if constexpr (g == 47) close_block(std::integral_constant<int, 0>{});
