@@ -9,21 +9,20 @@
 //
 // With a single wavefront per SIMD nothing but the instruction stream itself overlaps the vector
 // ALU (exponentials) with the matrix cores, so the loop is software-pipelined over 32-token blocks.
-// For tile t (blocks 0 and 1) a step runs four phases of 16 matrix instructions each, every one
-// interleaved with one row block's worth of softmax weights:
-//     1  S0(t)   = K0 Q^T          ||  weights of block 1 of tile t-1, row block 1
-//        reference(block 0)
-//     2  O      += V1(t-1)^T P1    ||  weights of block 0, row block 0
-//        (accumulator rescale if the reference rose)
-//     3  S1(t)   = K1 Q^T          ||  weights of block 0, row block 1
-//        reference(block 1)
-//     4  O      += V0(t)^T P0      ||  weights of block 1, row block 0
-//        (rescale)
-// so the output product of a tile's second block runs one step late, from the LDS buffer the next
-// step has not yet overwritten.  The matrix instructions are written as inline assembly to pin the
-// score tiles to vector registers and the accumulators to accumulation registers; the wait states
-// the hardware needs between a matrix instruction and a vector-ALU access to its result, which the
-// compiler cannot insert for inline assembly, are spelled out (settle_*).
+// For tile t (blocks 0 and 1) a step runs four phases of 16 matrix instructions each:
+//     1  S0(t)   = K0 Q^T
+//     2  O      += V1(t-1)^T P1      (the output product of a tile's second block runs one step
+//     3  S1(t)   = K1 Q^T             late, from an LDS buffer the next step has not overwritten)
+//     4  O      += V0(t)^T P0
+// and every matrix instruction is followed by an even share of all the other work of the step: one
+// half-piece of softmax weights (block 0 under phases 2-3, block 1 under phase 4 and phase 1 of the
+// next step), an operand fetch from LDS, a piece of the staging of the next tile.  The softmax keeps
+// no running maximum on this path: weights are taken against a reference that is only checked, per
+// block, to have kept the block's sums in range (see close_block).  The matrix instructions are
+// written as inline assembly to pin the score tiles to vector registers and the accumulators to
+// accumulation registers; the wait states the hardware needs between a matrix instruction and a
+// vector-ALU access to its result, which the compiler cannot insert for inline assembly, are spelled
+// out (settle_*).
 #include "prefill_tile.h"
 
 namespace diffqkv {
@@ -279,7 +278,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   };
 
   // One tile step; see the header for the phase order.  MASKED (compile time) adds the causal / length
-  // select to the two reference computations, the only place that looks at token positions.
+  // select on the finished score blocks, the only place that looks at token positions.
   int vcur = 0, vprev = 0;  // V^T buffers of this step's tile and of the one before (it % 3, (it - 1) % 3)
   bool pending = false;     // the previous tile's second block still waits for its output product
   auto tile_step = [&](int it, auto masked_tag) {

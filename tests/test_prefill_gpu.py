@@ -63,6 +63,22 @@ def test_every_mfma_variant(variant):
     run(inputs.config("prefill_8k", B=1, n_q=2, n_k=1, n_v=1, S=130, S_k=131, index=75), variant=variant)
 
 
+@pytest.mark.parametrize("variant", [0, 8])
+def test_wide_score_range_moves_the_softmax_reference(variant):
+    """Unit softmax scale on N(0,1) data of width 128 (scores of standard deviation ~11, spread over more
+    than a hundred log2 units), and rows whose largest score arrives late: the reference of the online
+    softmax has to rise several times on the way, also in the middle of a sequence."""
+    cfg = inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, S=900, index=76)
+    d = inputs.make_prefill(cfg)
+    d["k"][:, :, 517] *= 6.0   # one token that dominates every later row ...
+    d["k"][:, :, 100] *= -6.0  # ... and one that nearly vanishes
+    binding.diffqkv_set_tuning(prefill_waves=variant)
+    out, lse = binding.diffqkv_prefill(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]), scale=1.0, want_lse=True)
+    ref, ref_lse = oracle.prefill(inputs.as_numpy(d["q"]), inputs.as_numpy(d["k"]), inputs.as_numpy(d["v"]), scale=1.0)
+    util.check(out, ref, "bf16", "variant %d" % variant)
+    util.check_lse(lse, ref_lse)
+
+
 def test_generic_kernel_matches_too():
     run(inputs.config("prefill_8k", B=1, S=300, index=71), force_generic=True)
 
