@@ -103,17 +103,18 @@ __global__ __launch_bounds__(NW * 64, QB == 2 ? 1 : 2) void prefill_mfma_kernel(
   u32x4 st[kStage];
   u32x4* const kst = st + ((NW == 4) ? 4 : 0);
   auto load_tile = [&](int t0) {
-    // tile starts, wavefront-uniform: they travel in scalar registers
+    // (the tile start is part of the per-lane offset, which is what the bounds check that turns rows
+    //  past the end of the head into zeros is documented to cover)
     // with 8 wavefronts the roles are exclusive (if / else), so sharing the registers is safe
     if (k_role) {
 #pragma unroll
       for (int i = 0; i < KLD; ++i)
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kKThreads + kt) * 16, t0 * (DQK * 2), 0);
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kKThreads + kt) * 16 + t0 * (DQK * 2), 0, 0);
     }
     if ((NW == 4 || !k_role) && v_role) {
 #pragma unroll
       for (int x = 0; x < 4; ++x)
-        st[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2), t0 * (DV * 2), 0);
+        st[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2) + t0 * (DV * 2), 0, 0);
     }
   };
   auto store_tile = [&](int buf) {
@@ -339,12 +340,13 @@ __global__ __launch_bounds__(NW * 64, QB == 2 ? 1 : 2) void prefill_mfma_kernel(
 
 }  // namespace
 
-// bf16, head widths of 64 or 128 (d_qk <= d_v), and a K/V head no longer than the 2 GiB buffer window.
+// bf16, head widths of 64 or 128 (d_qk <= d_v), and a K/V head -- plus the tiles the staging loads run
+// past its end -- inside the 2 GiB window of 32-bit buffer offsets.
 bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
   if (dtype != 1) return false;
   const bool ok = (p.d_qk == 128 && p.d_v == 128) || (p.d_qk == 64 && p.d_v == 64) || (p.d_qk == 64 && p.d_v == 128);
   if (!ok) return false;
-  return (int64_t)p.S_k * p.d_v * 2 < (1ll << 31);
+  return (int64_t)(p.S_k + 2 * kBN) * p.d_v * 2 < (1ll << 31);
 }
 
 namespace {

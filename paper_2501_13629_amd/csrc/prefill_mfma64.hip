@@ -134,13 +134,13 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   auto load_k_tile = [&](int t0) {
 #pragma unroll
     for (int i = 0; i < KLD; ++i)
-      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kThreads + tid) * 16, t0 * (DQK * 2), 0);
+      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kThreads + tid) * 16 + t0 * (DQK * 2), 0, 0);
   };
   auto load_v_tile = [&](int t0) {
     if (v_role) {
 #pragma unroll
       for (int x = 0; x < 4; ++x)
-        vst[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2), t0 * (DV * 2), 0);
+        vst[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2) + t0 * (DV * 2), 0, 0);
     }
   };
   auto load_tile = [&](int t0) {

@@ -54,8 +54,10 @@ struct Smem {
   uint16_t vt[2][DV][kBN];
 };
 
-// Raw buffer resource over `bytes` bytes: loads take a scalar byte offset (the tile start) on top
-// of a loop-invariant per-lane offset, and rows past the end of the tensor read as zero.
+// Raw buffer resource over `bytes` bytes: a load whose per-lane offset (vector register plus
+// immediate) falls past the end reads as zero.  The kernels rely on that for rows past the end of a
+// head, so the tile start travels in the per-lane offset and the scalar offset stays zero: the
+// per-lane part is the one the range check is documented to cover.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);

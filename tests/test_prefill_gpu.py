@@ -79,6 +79,28 @@ def test_wide_score_range_moves_the_softmax_reference(variant):
     util.check_lse(lse, ref_lse)
 
 
+@pytest.mark.parametrize("variant", [0, 4, 8])
+def test_memory_behind_the_tensors_is_never_used(variant):
+    """K and V sit at the front of larger allocations whose remainder is NaN, and the lengths end inside a
+    tile: whatever the staging loads fetch past the last row of the last head -- in this tile or in the
+    tiles a kernel loads ahead -- must not reach the output (NaN times a zero weight is still NaN)."""
+    for S, S_k in ((37, 37), (300, 300), (130, 451)):
+        cfg = inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, S=S, S_k=S_k, index=77)
+        d = inputs.make_prefill(cfg)
+        dev = {}
+        for name in ("k", "v"):
+            t = d[name]
+            buf = torch.full((t.numel() + 3 * 64 * t.shape[-1],), float("nan"), dtype=t.dtype, device="cuda")
+            buf[:t.numel()] = t.reshape(-1).cuda()
+            dev[name] = buf[:t.numel()].view(t.shape)
+        binding.diffqkv_set_tuning(prefill_waves=variant)
+        out, lse = binding.diffqkv_prefill(util.dev(d["q"]), dev["k"], dev["v"], want_lse=True)
+        torch.cuda.synchronize()
+        ref, ref_lse = oracle.prefill(inputs.as_numpy(d["q"]), inputs.as_numpy(d["k"]), inputs.as_numpy(d["v"]))
+        util.check(out, ref, "bf16", "variant %d, S=%d, S_k=%d" % (variant, S, S_k))
+        util.check_lse(lse, ref_lse)
+
+
 def test_generic_kernel_matches_too():
     run(inputs.config("prefill_8k", B=1, S=300, index=71), force_generic=True)
 
