@@ -117,8 +117,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   }
 
   // ---- global -> register -> LDS staging of one K/V tile (every thread takes part in both) ----------
-  // K tile = 64 rows x d_qk channels = one contiguous run of 16-byte pieces; thread t takes pieces
-  // t, t + 256, ...  V tile: 16 token quads x d_v/8 channel chunks, one (quad, chunk) per thread: it
+  // K tile = 64 rows x d_qk channels: 16 threads share a row (16 bytes each) and take KLD rows next
+  // to each other, so one per-lane offset per tile serves all of a thread's loads through the
+  // immediate field.  V tile: 16 token quads x d_v/8 channel chunks, one (quad, chunk) per thread: it
   // loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to high:
   // chunk[2:0], quad-order bit 1, chunk[3] (d_v = 128 only), quad-order bit 0, 16-token group -- lanes
   // that write the same channel rows in one instruction differ in the half-granule they write.
@@ -130,11 +131,14 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
   const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
   const int v_voff = (4 * v_tq) * (DV * 2) + v_c8 * 16;
+  static_assert(DQK / 8 == 16 && kThreads / 16 * KLD == kBN, "16 threads per K row");
+  const int k_row = (tid >> 4) * KLD, k_chunk = tid & 15;
+  const int k_voff = k_row * (DQK * 2) + k_chunk * 16;
   u32x4 kst[KLD], vst[4];
   auto load_k_tile = [&](int t0) {
 #pragma unroll
     for (int i = 0; i < KLD; ++i)
-      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (i * kThreads + tid) * 16 + t0 * (DQK * 2), 0, 0);
+      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, k_voff + t0 * (DQK * 2) + i * (DQK * 2), 0, 0);
   };
   auto load_v_tile = [&](int t0) {
     if (v_role) {
@@ -148,8 +152,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     load_v_tile(t0);
   };
   auto store_k_item = [&](int i, int buf) {  // i in [0, KLD)
-    const int piece = i * kThreads + tid;
-    *(u32x4*)&sm.k[buf][piece / (DQK / 8)][(piece % (DQK / 8)) * 8] = kst[i];
+    *(u32x4*)&sm.k[buf][k_row + i][k_chunk * 8] = kst[i];
   };
   auto store_v_item = [&](int e, int vbuf) {  // channel e in [0, 8) of this thread's chunk
     if (v_role) {
