@@ -61,12 +61,25 @@ __device__ __forceinline__ void settle_a(f32x16 (&acc)[2][CB]) {
   }
 }
 
-// K double-buffered, V^T triple-buffered: the output product of a tile's second block runs during the
-// next step, while the staging stores of the step after that are already being written.
+// Tile t lives in buffer t % 3, K and V^T alike.  V^T needs three: the output product of a tile's
+// second block runs during the next step, while the staging stores of the step after that are already
+// being written.  K needs two and takes three so that both rotate together: the step body is compiled
+// once per buffer index, which turns every LDS address in it into a loop-invariant register plus an
+// immediate.
+// A tile buffer index that is either a compile-time constant (std::integral_constant) or a plain int.
+template <typename T>
+__device__ __forceinline__ constexpr int buffer_index(T t) {
+  if constexpr (std::is_integral_v<T>) return t;
+  else return T::value;
+}
+
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+
 template <int DQK, int DV>
 struct Smem64 {
   static constexpr int kKPitch = DQK + 8;  // bf16 elements per K row (16 B of padding)
-  uint16_t k[2][kBN][kKPitch];
+  uint16_t k[3][kBN][kKPitch];
   uint16_t vt[3][DV][kBN];
 };
 
@@ -154,23 +167,29 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   auto store_k_item = [&](int i, int buf) {  // i in [0, KLD)
     *(u32x4*)&sm.k[buf][k_row + i][k_chunk * 8] = kst[i];
   };
+  // The V^T store of channel e of this thread's chunk goes to row 8 v_c8 + e, granule (pos >> 3) ^
+  // swizzle(row) = (pos >> 3) ^ (v_c8 & 7) ^ e: a per-lane byte offset with e XORed into bits 4-6
+  // (they hold nothing else: the row pitch is 128 bytes and pos & 7 < 8 elements = 16 bytes).
+  const int v_pos = vt_pos(4 * v_tq);
+  // (LDS addresses as integers, with the start of the V^T buffers folded into the per-lane part: the
+  //  immediate field of an LDS instruction reaches 64 KiB from there, which covers all three buffers)
+  const uint32_t vt_base = (uint32_t)(uintptr_t)&sm.vt[0][0][0];
+  const uint32_t v_st = vt_base + (uint32_t)(v_c8 * 8 * (kBN * 2) + ((((v_pos >> 3) ^ v_c8) & 7) << 4) + (v_pos & 7) * 2);
   auto store_v_item = [&](int e, int vbuf) {  // channel e in [0, 8) of this thread's chunk
     if (v_role) {
-      const int pos = vt_pos(4 * v_tq);
       // word e/2, low or high half, from the 4 tokens
       const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
       u32x2 w;
       w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
       w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
-      const int ch = v_c8 * 8 + e;
-      *(u32x2*)&sm.vt[vbuf][ch][(((pos >> 3) ^ vt_swizzle(ch)) << 3) + (pos & 7)] = w;
+      *(lds_u32x2*)((v_st ^ (uint32_t)(e << 4)) + (uint32_t)((vbuf * DV + e) * (kBN * 2))) = w;
     }
   };
-  auto store_tile = [&](int buf, int vbuf) {
+  auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < KLD; ++i) store_k_item(i, buf);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) store_v_item(e, vbuf);
+    for (int e = 0; e < 8; ++e) store_v_item(e, buf);
   };
 
   // ---- state ----------------------------------------------------------------------------------------
@@ -194,8 +213,12 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   settle_a<CB>(acc);
 
   load_tile(0);
-  store_tile(0, 0);
-  if (n_tiles > 1) load_tile(kBN);  // staging registers always hold the tile after the one in LDS
+  store_tile(0);
+  load_tile(kBN);  // staging registers always hold the tile after the one in LDS
+  // the first step runs the "previous tile" output product with weights of zero, from buffer 2: make
+  // what it multiplies finite
+#pragma unroll
+  for (int i = 0; i < DV * kBN * 2 / 16 / kThreads; ++i) ((u32x4*)&sm.vt[2][0][0])[i * kThreads + tid] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -274,24 +297,37 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       l_blk[blk][qb] = 0.f;
     }
   };
-  // V^T fragment of 16-token step kq, channel block cb, from tile buffer vb
-  auto vt_frag = [&](int vb, int kq, int cb) {
-    const int ch = 32 * cb + n;
-    return *(const u32x4*)&sm.vt[vb][ch][((2 * kq + half) ^ vt_swizzle(ch)) << 3];
+  // V^T fragment of 16-token step kq, channel block cb, from tile buffer vb: row 32 cb + n, granule
+  // (2 kq + half) ^ swizzle(row).  The swizzle of row 32 cb + n is that of row n with bit 2 flipped for
+  // odd cb, and 2 kq only sets bits 1-2, so the granule is (swizzle(n) ^ half) ^ C with C = 2 kq ^
+  // 4 (cb & 1), one of 0, 2, 4, 6: four per-lane byte offsets serve every fragment, the rest of the
+  // address is an immediate.
+  uint32_t vt_lane[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) vt_lane[c] = vt_base + (uint32_t)(n * (kBN * 2) + (((vt_swizzle(n) ^ half) ^ (2 * c)) << 4));
+  auto vt_frag = [&](int vb, auto kqc, auto cbc) {  // (vb: a constant wherever the caller's is)
+    constexpr int kq = decltype(kqc)::value, cb = decltype(cbc)::value;
+    constexpr int c = ((2 * kq) ^ (4 * (cb & 1))) / 2;
+    return *(const lds_u32x4*)(vt_lane[c] + (uint32_t)((vb * DV + 32 * cb) * (kBN * 2)));
   };
 
   // One tile step; see the header for the phase order.  MASKED (compile time) adds the causal / length
   // select on the finished score blocks, the only place that looks at token positions.
-  int vcur = 0, vprev = 0;  // V^T buffers of this step's tile and of the one before (it % 3, (it - 1) % 3)
-  bool pending = false;     // the previous tile's second block still waits for its output product
-  auto tile_step = [&](int it, auto masked_tag) {
+  bool pending = false;  // the previous tile's second block still waits for its output product
+  // A step of a wavefront that is past its last row: it only helps staging.
+  auto staging_step = [&](int it, int cur) {
+    const int next = cur == 2 ? 0 : cur + 1;
+    store_tile(next);
+    load_tile(it * kBN + 2 * kBN);
+    __syncthreads();
+  };
+  // curc = it % 3, the buffer of this step's tile: an int, or a std::integral_constant -- then every
+  // LDS address of the step is a loop-invariant register plus an immediate.
+  auto tile_step = [&](int it, auto masked_tag, auto curc) {
     constexpr bool MASKED = decltype(masked_tag)::value;
-    const int t0 = it * kBN, buf = it & 1;
-    const bool more = it + 1 < n_tiles, more2 = it + 2 < n_tiles;
-    const int vnext = vcur == 2 ? 0 : vcur + 1;
-
-    if (t0 < wave_limit) {
-      const int vold = pending ? vprev : vcur;  // first step: weights are zero, any finite V will do
+    const int cur = buffer_index(curc), next = cur == 2 ? 0 : cur + 1, prev = cur == 0 ? 2 : cur - 1;
+    const int t0 = it * kBN;
+    {
       // fragment order: K block 0 | V^T of the previous tile's block 1 | K block 1 | V^T block 0
       constexpr int G0 = KS, G1 = KS + 2 * CB, G2 = 2 * KS + 2 * CB, kFrags = 2 * KS + 4 * CB;
       constexpr int kRing = 8;
@@ -299,16 +335,16 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       auto fetch = [&](auto fc) {
         constexpr int f = decltype(fc)::value;
         if constexpr (f < G0) {
-          fr[f % kRing] = *(const u32x4*)&sm.k[buf][n][16 * f + 8 * half];
+          fr[f % kRing] = *(const u32x4*)&sm.k[cur][n][16 * f + 8 * half];
         } else if constexpr (f < G1) {
           constexpr int j = f - G0;
-          fr[f % kRing] = vt_frag(vold, 2 + j / CB, j % CB);
+          fr[f % kRing] = vt_frag(prev, std::integral_constant<int, 2 + j / CB>{}, std::integral_constant<int, j % CB>{});
         } else if constexpr (f < G2) {
           constexpr int ks = f - G1;
-          fr[f % kRing] = *(const u32x4*)&sm.k[buf][32 + n][16 * ks + 8 * half];
+          fr[f % kRing] = *(const u32x4*)&sm.k[cur][32 + n][16 * ks + 8 * half];
         } else {
           constexpr int j = f - G2;
-          fr[f % kRing] = vt_frag(vcur, j / CB, j % CB);
+          fr[f % kRing] = vt_frag(cur, std::integral_constant<int, j / CB>{}, std::integral_constant<int, j % CB>{});
         }
       };
       static_for<0, kRing>(fetch);
@@ -346,8 +382,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         constexpr int idx = decltype(ic)::value;
         // (unconditional: past the last tile the stores park stale registers in a buffer nobody
         //  reads, and the loads fall outside the buffer resource and return zeros)
-        if constexpr (idx < KLD) store_k_item(idx, buf ^ 1);
-        else if constexpr (idx < KLD + 8) store_v_item(idx - KLD, vnext);
+        if constexpr (idx < KLD) store_k_item(idx, next);
+        else if constexpr (idx < KLD + 8) store_v_item(idx - KLD, next);
         else if constexpr (idx == KLD + 8) load_k_tile(t0 + 2 * kBN);
         else load_v_tile(t0 + 2 * kBN);
       };
@@ -390,29 +426,23 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         __builtin_amdgcn_sched_barrier(0);
       });
       pending = true;
-    } else {
-      if (more) store_tile(buf ^ 1, vnext);
-      if (more2) load_tile(t0 + 2 * kBN);
     }
-    vprev = vcur;
-    vcur = vnext;
     __syncthreads();
   };
   // The block that is still in flight after the last step a wavefront computes.
-  auto drain = [&]() {
+  auto drain = [&](int vprev) {  // vprev: buffer of the last tile computed
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
       for (int i = 4; i < 8; ++i) weights_piece(1, qb, i);  // the halves the next step would have taken
     close_block(std::integral_constant<int, 1>{});
-#pragma unroll
-    for (int j = 0; j < 2 * CB; ++j) {
-      const u32x4 a = vt_frag(vprev, 2 + j / CB, j % CB);
-      const int sh = (j / CB) * 4;
+    static_for<0, 2 * CB>([&](auto jc) {
+      constexpr int j = decltype(jc)::value, sh = (j / CB) * 4;
+      const u32x4 a = vt_frag(vprev, std::integral_constant<int, 2 + j / CB>{}, std::integral_constant<int, j % CB>{});
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
         mfma_a(acc[qb][j % CB], a, u32x4{pw[qb][1][sh], pw[qb][1][sh + 1], pw[qb][1][sh + 2], pw[qb][1][sh + 3]});
-    }
+    });
     pending = false;
   };
 
@@ -427,11 +457,19 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   int n_compute = wave_limit > 0 ? (wave_limit + kBN - 1) / kBN : 0;
   n_compute = n_compute < n_tiles ? n_compute : n_tiles;
   n_plain = n_plain < n_compute ? n_plain : n_compute;
+  // The bulk of the steps -- unmasked, three at a time, one per buffer -- run with constant buffer
+  // indices; what is left over, and the masked steps around the diagonal, take the index as a value.
   int it = 0;
-  for (; it < n_plain; ++it) tile_step(it, std::false_type{});
-  for (; it < n_compute; ++it) tile_step(it, std::true_type{});
-  if (pending) drain();
-  for (; it < n_tiles; ++it) tile_step(it, std::true_type{});  // staging only (t0 >= wave_limit)
+  for (; it + 3 <= n_plain; it += 3) {
+    tile_step(it, std::false_type{}, std::integral_constant<int, 0>{});
+    tile_step(it + 1, std::false_type{}, std::integral_constant<int, 1>{});
+    tile_step(it + 2, std::false_type{}, std::integral_constant<int, 2>{});
+  }
+  int cur = 0;  // it % 3
+  for (; it < n_plain; ++it, cur = cur == 2 ? 0 : cur + 1) tile_step(it, std::false_type{}, cur);
+  for (; it < n_compute; ++it, cur = cur == 2 ? 0 : cur + 1) tile_step(it, std::true_type{}, cur);
+  if (pending) drain(cur == 0 ? 2 : cur - 1);
+  for (; it < n_tiles; ++it, cur = cur == 2 ? 0 : cur + 1) staging_step(it, cur);  // (t0 >= wave_limit from here on)
 
   // ---- write this wavefront's rows: lane (half, n), acc[qb][cb][r] = row 32 qb + n, channel
   //      32 cb + 8 (r/4) + 4 half + r%4.  Both halves hold the full row sum after the exchange.
