@@ -396,8 +396,12 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         if constexpr (g < 16) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 16 + g>{}, tp);
         if constexpr (g == 15) close_block(std::integral_constant<int, 1>{});  // the previous tile's second block
         if constexpr (g == 47) close_block(std::integral_constant<int, 0>{});
-        if constexpr ((g & 1) && g < 16) stage_item(std::integral_constant<int, g / 2>{});
-        if constexpr ((g & 1) && g >= 25 && g < 25 + 2 * (KLD + 10 - 8)) stage_item(std::integral_constant<int, 8 + (g - 25) / 2>{});
+        // staging on odd slots: the K stores, then at once the K loads of the tile after (the longer a
+        // load has before its store, a step later, the less that store waits), the V stores, the V loads
+        if constexpr ((g & 1) && g < 2 * KLD) stage_item(std::integral_constant<int, g / 2>{});
+        if constexpr (g == 2 * KLD + 1) stage_item(std::integral_constant<int, KLD + 8>{});
+        if constexpr ((g & 1) && g >= 2 * KLD + 3 && g < 2 * KLD + 3 + 16) stage_item(std::integral_constant<int, KLD + (g - 2 * KLD - 3) / 2>{});
+        if constexpr (g == 2 * KLD + 3 + 16) stage_item(std::integral_constant<int, KLD + 9>{});
       };
 
       static_for<0, kFrags>([&](auto fc) {
