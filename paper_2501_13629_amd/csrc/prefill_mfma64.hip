@@ -370,12 +370,12 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         settle_v(s[0][blk], s[1][blk]);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-          const int row_limit = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;
+          // register r is allowed iff 8 (r/4) + r%4 <= lim: one compare against a constant per register
+          int last = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;  // last token this row may see
+          last = last < p.S_k - 1 ? last : p.S_k - 1;
+          const int lim = last - (t0 + 32 * blk + 4 * half);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int tok = t0 + 32 * blk + 8 * (r >> 2) + 4 * half + (r & 3);
-            s[qb][blk][r] = (tok <= row_limit && tok < p.S_k) ? s[qb][blk][r] : -INFINITY;
-          }
+          for (int r = 0; r < 16; ++r) s[qb][blk][r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[qb][blk][r] : -INFINITY;
         }
       };
       auto stage_item = [&](auto ic) {
@@ -462,7 +462,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   n_compute = n_compute < n_tiles ? n_compute : n_tiles;
   n_plain = n_plain < n_compute ? n_plain : n_compute;
   // The bulk of the steps -- unmasked, three at a time, one per buffer -- run with constant buffer
-  // indices; what is left over, and the masked steps around the diagonal, take the index as a value.
+  // indices; the one or two unmasked steps that may be left over share the body of the masked steps
+  // around the diagonal (its selects pass everything there), which takes the index as a value: one
+  // more copy of the step for them would cost more in instruction-cache misses than the selects do.
   int it = 0;
   for (; it + 3 <= n_plain; it += 3) {
     tile_step(it, std::false_type{}, std::integral_constant<int, 0>{});
@@ -470,7 +472,6 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     tile_step(it + 2, std::false_type{}, std::integral_constant<int, 2>{});
   }
   int cur = 0;  // it % 3
-  for (; it < n_plain; ++it, cur = cur == 2 ? 0 : cur + 1) tile_step(it, std::false_type{}, cur);
   for (; it < n_compute; ++it, cur = cur == 2 ? 0 : cur + 1) tile_step(it, std::true_type{}, cur);
   if (pending) drain(cur == 0 ? 2 : cur - 1);
   for (; it < n_tiles; ++it, cur = cur == 2 ? 0 : cur + 1) staging_step(it, cur);  // (t0 >= wave_limit from here on)
