@@ -476,27 +476,40 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   if (pending) drain(cur == 0 ? 2 : cur - 1);
   for (; it < n_tiles; ++it, cur = cur == 2 ? 0 : cur + 1) staging_step(it, cur);  // (t0 >= wave_limit from here on)
 
-  // ---- write this wavefront's rows: lane (half, n), acc[qb][cb][r] = row 32 qb + n, channel
-  //      32 cb + 8 (r/4) + 4 half + r%4.  Both halves hold the full row sum after the exchange.
+  // ---- write this wavefront's rows.  Lane (half, n) holds row 32 qb + n in pieces of four channels
+  //      (acc[qb][cb][r]: channel 32 cb + 8 (r/4) + 4 half + r%4); stored from there, one instruction
+  //      would touch 32 rows.  So each row block passes through a slice of LDS that belongs to this
+  //      wavefront alone (inside the K buffers: every wavefront has left the step loop through its
+  //      last barrier, and what may still run elsewhere, the drain, reads V^T only) and leaves in 16-byte
+  //      pieces, 16 lanes to a row: whole 256-byte rows per store.  The LDS operations of one
+  //      wavefront execute in order, so the slice needs no barrier.
   settle_a<CB>(acc);
+  constexpr int kOutPitch = DV * 2 + 8;  // bytes per row in the slice; the 8 spread the rows over the banks
+  static_assert(4 * 32 * kOutPitch <= (int)sizeof(sm.k), "four slices fit in the K buffers");
+  char* const slice = (char*)&sm.k[0][0][0] + wave * (32 * kOutPitch);
+  const int o_row = lane >> 4, o_chunk = lane & 15;
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
     const int my_row = r0 + 32 * qb + n;
-    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-    if (my_row < p.S_q) {
-      const float inv = 1.f / l;
-      uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + my_row) * DV;
+    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);  // both halves hold the full row sum now
+    const float inv = 1.f / l;
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          u32x2 w;
-          w[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
-          w[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
-          *(u32x2*)(orow + 32 * cb + 8 * q4 + 4 * half) = w;
-        }
-      if (half == 0 && p.lse_out)
-        p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
+      for (int q4 = 0; q4 < 4; ++q4) {
+        u32x2 w;
+        w[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
+        w[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
+        *(u32x2*)(slice + n * kOutPitch + (32 * cb + 8 * q4 + 4 * half) * 2) = w;
+      }
+    if (my_row < p.S_q && half == 0 && p.lse_out)
+      p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
+    uint16_t* const oblock = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + r0 + 32 * qb) * DV;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + o_row;
+      const u32x4 piece = *(const u32x4*)(slice + row * kOutPitch + o_chunk * 16);
+      if (r0 + 32 * qb + row < p.S_q) *(u32x4*)(oblock + row * DV + o_chunk * 8) = piece;
     }
   }
 }
