@@ -22,7 +22,10 @@
 // written as inline assembly to pin the score tiles to vector registers and the accumulators to
 // accumulation registers; the wait states the hardware needs between a matrix instruction and a
 // vector-ALU access to its result, which the compiler cannot insert for inline assembly, are spelled
-// out (settle_*).
+// out (settle_*).  In the other direction -- a vector write needs two wait states before a matrix
+// instruction may read the register -- no operand is produced right in front of its consumer:
+// fragments arrive from LDS behind a wait, weights are packed at least a slot earlier
+// (tests/test_prefill_codegen.py checks the compiled instruction stream for this).
 #include "prefill_tile.h"
 
 namespace diffqkv {
