@@ -269,7 +269,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   auto close_block = [&](auto blkc) {
     constexpr int blk = decltype(blkc)::value;
     const float worst = fmaxf(l_blk[blk][0], l_blk[blk][1]);
-    if (__builtin_amdgcn_ballot_w64(!(worst <= kBig))) {  // (a NaN also lands here, and stays a NaN)
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(worst <= kBig)) != 0, 0)) {  // (a NaN also lands here, and stays a NaN)
       settle_a<CB>(acc);
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
