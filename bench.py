@@ -11,8 +11,13 @@ last-level cache cannot serve a step from what the previous one left behind.
 
 Prints one JSON line.  `value` is whole-job throughput: KV-cache bytes read per second (decode) or
 attention TFLOP/s (prefill), from the wall clock around exactly K steps.  `roofline` is for the
-dominant kernel alone, timed with HIP events recorded on the launch stream; `cpu_baseline` is the
-float64 oracle on the host cores, for context only.
+dominant kernel alone, timed with HIP events recorded on the launch stream (an event pair costs a few
+microseconds of its own: the cost of an empty pair is measured in the same run and subtracted, both
+figures are printed); `cpu_baseline` is the float64 oracle on the host cores, for context only.
+
+Without `--workload` the line is the headline workload (decode_32k) and carries an `also` object with
+the other three attention workloads (prefill_8k, decode_4k, paged_ragged), each timed the same way
+with a fixed, smaller number of steps.
 """
 import argparse
 import json
@@ -33,17 +38,21 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode_32k",
+    ap.add_argument("--workload", default=None,
                     choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k", "augq_1p5b", "augq_10b"],
                     help="the last two time the augmented-Q feed-forward of a decode step (16 tokens) at "
                          "Sigma-1.5B / Sigma-10B widths: weight bytes per second")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true", help="default run: headline workload only")
     ap.add_argument("--top-k", type=int, default=-1,
                     help="contiguous decode workloads only: selective V-cache fetching with this top_k "
                          "(a different, smaller byte count; not the headline metric)")
     ap.add_argument("--prefill-waves", type=int, default=0, help="prefill kernel variant (experiments)")
     ap.add_argument("--chunk", type=int, default=0, help="override tokens per context split (experiments)")
     return ap.parse_args()
+
+
+ALSO = (("prefill_8k", 30, 5), ("decode_4k", 200, 20), ("paged_ragged", 30, 5))  # (workload, steps, warm-up)
 
 
 def main():
@@ -62,16 +71,41 @@ def main():
     binding.load_library()  # fail loudly if the HIP library is not built
     binding.diffqkv_set_tuning(decode_chunk_tokens=args.chunk, prefill_waves=args.prefill_waves)
     dev = torch.device("cuda:0")
-    if args.workload.startswith("augq"):
+    headline = args.workload or "decode_32k"
+    if headline.startswith("augq"):
         return bench_augq(args, torch, binding, inputs, dev)
-    cfg = inputs.config(args.workload)
-    kind = cfg["kind"]
-    topk = args.top_k
-    if topk >= 0 and kind != "decode":
+    if args.top_k >= 0 and inputs.config(headline)["kind"] != "decode":
         print("bench.py: --top-k goes with the contiguous decode workloads", file=sys.stderr)
         sys.exit(2)
-    props = torch.cuda.get_device_properties(0)
+    line = run_workload(headline, args.steps, args.warmup, args.top_k, not args.no_cpu_baseline, torch, binding,
+                        inputs, dev)
+    if args.workload is None and args.top_k < 0 and not args.no_also:
+        also = {}
+        for name, steps, warmup in ALSO:
+            r = run_workload(name, steps, warmup, -1, False, torch, binding, inputs, dev)
+            also[name] = {k: r[k] for k in ("metric", "value", "unit", "steps", "warmup", "ms_per_step")}
+            also[name]["roofline"] = r["roofline"]
+            also[name]["config"] = r["config"]
+        line["also"] = also
+    print(json.dumps(line))
 
+
+def event_pair_overhead_us(torch, n=200):
+    """What two events recorded back to back on the current stream read, with nothing between them."""
+    a = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+    b = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+    for x, y in zip(a, b):
+        x.record()
+        y.record()
+    torch.cuda.synchronize()
+    us = sorted(x.elapsed_time(y) * 1e3 for x, y in zip(a, b))
+    return us[len(us) // 2]
+
+
+def run_workload(workload, steps, warmup, topk, want_cpu, torch, binding, inputs, dev):
+    cfg = inputs.config(workload)
+    kind = cfg["kind"]
+    props = torch.cuda.get_device_properties(0)
     # ---- inputs, resident on the device ----------------------------------------------------------
     if kind == "decode":
         host = inputs.make_decode(cfg)
@@ -126,19 +160,19 @@ def main():
             binding.diffqkv_prefill(q, k_dev, v_dev, causal=True, out=out)
 
     # ---- warm-up, then exactly K timed steps -------------------------------------------------------
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
 
     # ---- the dominant kernel alone, with events on the launch stream ----------------------------------
     # decode: start event -> [split kernel] -> library-recorded event -> [combine] -> end event
-    n_ev = min(args.steps, 100)
+    n_ev = min(steps, 100)
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
     ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
     ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
@@ -157,7 +191,13 @@ def main():
     else:
         main_us = sorted(ev0[i].elapsed_time(ev2[i]) * 1e3 for i in range(n_ev))
         tail_us = [0.0]
-    avg_main_us = sum(main_us) / len(main_us)
+    # an event pair reads a few microseconds with nothing between its two records (the packets'
+    # own cost): measured here, subtracted from every bracketed figure, and printed
+    ev_overhead = event_pair_overhead_us(torch)
+    bracketed_main_us = sum(main_us) / len(main_us)
+    avg_main_us = max(bracketed_main_us - ev_overhead, 1e-3)
+    min_main_us = max(main_us[0] - ev_overhead, 1e-3)
+    avg_tail_us = max(sum(tail_us) / len(tail_us) - ev_overhead, 0.0) if tail_us != [0.0] else 0.0
 
     # ---- stream-read ceiling of this machine, over the same byte count -----------------------------------
     ceiling = None
@@ -187,8 +227,11 @@ def main():
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "kernel": "decode_mfma_kernel (split)" if topk < 0 else "topk_scores + topk_select (both)",
-                "kernel_avg_us": round(avg_main_us, 2),
-                "kernel_min_us": round(main_us[0], 2), "combine_avg_us": round(sum(tail_us) / len(tail_us), 2),
+                "kernel_avg_us": round(avg_main_us, 2), "kernel_min_us": round(min_main_us, 2),
+                "combine_avg_us": round(avg_tail_us, 2),
+                "kernel_avg_us_event_bracketed": round(bracketed_main_us, 2),
+                "event_pair_overhead_us": round(ev_overhead, 2),
+                "step_frac": round(value / HBM_PEAK_GBPS, 4),
                 "algorithmic_bytes_per_launch": kv_bytes,
                 "stream_read_ceiling_GBps": None if ceiling is None else round(ceiling, 1)}
     else:
@@ -197,29 +240,38 @@ def main():
         achieved = flops / (avg_main_us * 1e-6) / 1e12
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": "prefill kernel",
-                "kernel_avg_us": round(avg_main_us, 2), "kernel_min_us": round(main_us[0], 2),
+                "kernel_avg_us": round(avg_main_us, 2), "kernel_min_us": round(min_main_us, 2),
+                "kernel_avg_us_event_bracketed": round(bracketed_main_us, 2),
+                "event_pair_overhead_us": round(ev_overhead, 2),
+                "step_frac": round(value / BF16_PEAK_TFLOPS, 4),
                 "algorithmic_flops_per_launch": flops}
+    # HBM bytes per launch come from separate rocprofv3 --pmc runs of this same command (counters cannot
+    # be read from inside the process); the figure is a stored measurement, and says so
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc (see profiles/)
+    roof["traffic_source"] = None
+    if os.path.exists(traffic_file):
         with open(traffic_file) as f:
-            roof["traffic"] = json.load(f).get(args.workload if topk < 0 else "%s_topk%d" % (args.workload, topk))
+            roof["traffic"] = json.load(f).get(workload if topk < 0 else "%s_topk%d" % (workload, topk))
+        if roof["traffic"] is not None:
+            roof["traffic_source"] = ("stored: profiles/hbm_traffic.json, rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE "
+                                      "of an earlier run of this workload, not measured in this run")
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, host, kind, kv_bytes, topk)
+    cpu = cpu_baseline(cfg, host, kind, kv_bytes, topk) if want_cpu else None
 
     line = {
-        "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+        "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4) if kind != "prefill" else None,
-        "config": {"workload": args.workload if topk < 0 else "%s, top_k=%d" % (args.workload, topk), **{k: v for k, v in cfg.items()
+        "config": {"workload": workload if topk < 0 else "%s, top_k=%d" % (workload, topk), **{k: v for k, v in cfg.items()
                                                  if k in ("B", "n_q", "n_k", "n_v", "d_qk", "d_v", "T", "S", "page_size")},
                    "kv_bytes_per_step": kv_bytes, "cache_sets_in_rotation": n_sets,
                    "device": props.name, "compute_units": props.multi_processor_count},
         "roofline": roof, "cpu_baseline": cpu,
     }
-    print(json.dumps(line))
+    del sets, q, out
+    torch.cuda.empty_cache()
+    return line
 
 
 def bench_augq(args, torch, binding, inputs, dev):

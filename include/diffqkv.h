@@ -30,6 +30,13 @@
  *   - Return value: a diffqkv_status.  On any value other than DIFFQKV_OK nothing was enqueued.
  *     Errors raised asynchronously by the device surface at the caller's next synchronisation.
  *   - Results are a deterministic function of the arguments (no atomics in any reduction).
+ *   - Thread safety: the entry points share no mutable state; calls from different threads are
+ *     independent as long as they do not share output or workspace memory.  The only process-wide
+ *     state is a cache of device properties (the compute-unit count, read once per device, which
+ *     sizes the context split), so the *_workspace_bytes query and the call it sizes must run with
+ *     the same device current.
+ *
+ * Experimental knobs and measurement aids live in diffqkv_experimental.h.
  */
 #ifndef DIFFQKV_H_
 #define DIFFQKV_H_
@@ -51,7 +58,8 @@ typedef enum {
                                    the other                                                       */
   DIFFQKV_ERR_ALIGN = -4,       /* a base pointer or stride breaks 16-byte row alignment           */
   DIFFQKV_ERR_WORKSPACE = -5,   /* workspace is NULL or smaller than the *_workspace_bytes figure  */
-  DIFFQKV_ERR_UNSUPPORTED = -6, /* valid arguments this build has no kernel for                    */
+  DIFFQKV_ERR_UNSUPPORTED = -6, /* valid arguments this build has no kernel for (top_k above 512,
+                                   an augmented-Q product beyond 2^40 elements)                    */
   DIFFQKV_ERR_HIP = -7          /* a HIP call failed at launch time                                */
 } diffqkv_status;
 
@@ -67,21 +75,6 @@ typedef struct {
   int32_t dtype; /* diffqkv_dtype of q, the caches and out    */
   float softmax_scale;
 } diffqkv_shape;
-
-/* Optional knobs for experiments; zero fields mean "library default".  Process-global, not
- * thread-safe: set once before issuing work. */
-typedef struct {
-  int32_t decode_chunk_tokens; /* tokens per context split (multiple of 128)                      */
-  int32_t force_generic;       /* 1: always take the portable kernels instead of the MFMA ones    */
-  int32_t prefill_waves;       /* MFMA prefill variant: 0 choose; 8 or 4 wavefronts of 32 rows;  *
-                                * 2 = 4 wavefronts of 64 rows (d_qk = d_v = 128 only)             */
-  int32_t decode_ragged_mode;  /* work split of the MFMA decode kernel.  0: equal slices per
-                                  wavefront when seqlens is given, fixed-size chunks otherwise;
-                                  1: equal slices always; 2: fixed-size chunks always            */
-  int32_t decode_workers;      /* wavefronts launched by the equal-slice split (multiple of 4)   */
-  int32_t reserved[3];
-} diffqkv_tuning;
-void diffqkv_set_tuning(const diffqkv_tuning* t /* host; NULL resets */);
 
 /*
  * Split decode (section 3.2: "split kernel" producing per-chunk partial outputs, "combine kernel"
@@ -157,7 +150,7 @@ int diffqkv_prefill(const diffqkv_shape* shape /* host */, const void* q, const 
  * top_k = 100.
  *
  *   arguments as in diffqkv_decode / diffqkv_decode_paged, plus
- *   top_k        0 .. 512
+ *   top_k        0 .. 512 (more: DIFFQKV_ERR_UNSUPPORTED)
  *   sel_out      int32 [B, n_q, top_k + 1] on the device or NULL: the selected positions of every
  *                query head (unordered, unused entries -1)
  *   workspace    at least diffqkv_decode_topk_workspace_bytes(shape, T) bytes (fp32 scores
@@ -237,21 +230,6 @@ size_t diffqkv_augment_q_workspace_bytes(const diffqkv_augq_shape* shape /* host
 int diffqkv_augment_q(const diffqkv_augq_shape* shape /* host */, const void* q_in, const void* w_gate,
                       const void* w_up, const void* w_down, void* q_out, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
-
-/*
- * Measurement aid: reads `bytes` (a multiple of 16) from `src` with 128-bit loads, as fast as the
- * memory system allows, and writes one float per workgroup to `sink` (at least 4096 floats) so the
- * reads cannot be elided.  Used to measure the achievable HBM read rate beside the decode kernels.
- */
-int diffqkv_probe_stream_read(const void* src, size_t bytes, float* sink, void* hip_stream);
-
-/*
- * Measurement aid: when `hip_event` (a hipEvent_t passed as void*) is not NULL, every later decode
- * call records it on its stream between the split kernel and the combine kernel, so a caller that
- * brackets the call with two events of its own can time the two kernels separately.  NULL turns it
- * off.  Process-global, not thread-safe.
- */
-void diffqkv_set_split_event(void* hip_event);
 
 /* Human-readable text for a diffqkv_status (static storage). */
 const char* diffqkv_strerror(int status);

@@ -19,13 +19,16 @@ LIB_PATH = _PKG / "libdiffqkv.so"
 
 F32, BF16 = 0, 1
 
+# include/diffqkv.h
 EXPORTS = (
-    "diffqkv_set_tuning", "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_paged",
-    "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_probe_stream_read", "diffqkv_strerror",
-    "diffqkv_version", "diffqkv_set_split_event", "diffqkv_append", "diffqkv_append_paged",
+    "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_paged",
+    "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_strerror",
+    "diffqkv_version", "diffqkv_append", "diffqkv_append_paged",
     "diffqkv_decode_topk_workspace_bytes", "diffqkv_decode_topk", "diffqkv_decode_topk_paged",
     "diffqkv_augment_q_workspace_bytes", "diffqkv_augment_q",
 )
+# include/diffqkv_experimental.h (knobs and measurement aids; per calling thread)
+EXPERIMENTAL_EXPORTS = ("diffqkv_set_tuning", "diffqkv_set_split_event", "diffqkv_probe_stream_read")
 
 
 class Shape(ctypes.Structure):

@@ -38,7 +38,7 @@ def stale() -> bool:
     if not LIB.exists():
         return True
     t = LIB.stat().st_mtime
-    deps = [CSRC / s for s in SOURCES] + [CSRC / "kernels.h", CSRC / "prefill_tile.h", INCLUDE / "diffqkv.h", Path(__file__)]
+    deps = [CSRC / s for s in SOURCES] + [CSRC / "kernels.h", CSRC / "prefill_tile.h", INCLUDE / "diffqkv.h", INCLUDE / "diffqkv_experimental.h", Path(__file__)]
     return any(d.stat().st_mtime > t for d in deps)
 
 

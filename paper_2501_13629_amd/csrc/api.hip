@@ -3,21 +3,41 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "../../include/diffqkv.h"
+#include "../../include/diffqkv_experimental.h"
 #include "kernels.h"
 
 using namespace diffqkv;
 
 namespace {
 
-diffqkv_tuning g_tuning = {};
-hipEvent_t g_split_event = nullptr;
+// Experimental knobs are per thread: they change only the calls of the thread that set them, and the
+// product entry points share no mutable state between threads.
+thread_local diffqkv_tuning t_tuning = {};
+thread_local hipEvent_t t_split_event = nullptr;
 
-// Split plan, a pure function of the shapes.  Measured on MI355X: the decode kernel streams fastest
-// when the whole context fits one round of workgroups, one per compute unit, each as long as
-// possible (every extra round exposes a prologue and an epilogue with no loads in flight).
-constexpr int kComputeUnits = 256;
-constexpr int kTargetWorkgroups = kComputeUnits;
+// Compute units of the current device, read once per device.  Without a device (validation-only use
+// on a host without a GPU) the figure of the chip this library is built for stands in.
+constexpr int kDefaultComputeUnits = 256;
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_compute_units[kMaxDevices];
+int compute_units() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kDefaultComputeUnits;
+  int cu = g_compute_units[dev].load(std::memory_order_relaxed);
+  if (cu > 0) return cu;
+  if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
+    return kDefaultComputeUnits;
+  g_compute_units[dev].store(cu, std::memory_order_relaxed);
+  return cu;
+}
+
+// Split plan, a pure function of the shapes and of the device's compute-unit count.  Measured on
+// MI355X: the decode kernel streams fastest when the whole context fits one round of workgroups, one
+// per compute unit, each as long as possible (every extra round exposes a prologue and an epilogue
+// with no loads in flight).
 constexpr int kChunkQuantum = 128;  // one workgroup step of the decode kernels
 constexpr int kMinChunk = 128;
 constexpr int kMaxChunk = 8192;
@@ -50,12 +70,13 @@ float scale_log2(const diffqkv_shape* s) {
 // Context split: a pure function of the shapes so that results are repeatable bit for bit.
 void plan_decode(const diffqkv_shape* s, int32_t max_T, bool ragged, int32_t* chunk, int32_t* num_splits) {
   int c;
-  if (g_tuning.decode_chunk_tokens > 0) {
-    c = (g_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+  if (t_tuning.decode_chunk_tokens > 0) {
+    c = (t_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
   } else {
     const int groups = (s->n_k < s->n_v ? s->n_k : s->n_v) * (s->B > 0 ? s->B : 1);
     const int64_t total = (int64_t)max_T * groups;
-    int64_t per = (total + kTargetWorkgroups - 1) / kTargetWorkgroups;
+    const int target = compute_units();  // one workgroup per compute unit
+    int64_t per = (total + target - 1) / target;
     per = (per + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     const int hi = ragged ? kMaxChunkRagged : kMaxChunk;
     c = (int)(per < kMinChunk ? kMinChunk : (per > hi ? hi : per));
@@ -76,9 +97,8 @@ size_t workspace_for(const diffqkv_shape* s, int32_t num_splits) {
 // equal slices of the 32-token-unit space.  The smallest slice (and with it the number of partial
 // slots a row can need) is fixed from the host-side bound on the work, so that small batches still
 // spread over the whole chip while large ones keep the partial results few.
-constexpr int kStreamKWorkers = 2 * kComputeUnits * 4;
 int streamk_workers() {
-  return g_tuning.decode_workers > 0 ? (g_tuning.decode_workers + 3) / 4 * 4 : kStreamKWorkers;
+  return t_tuning.decode_workers > 0 ? (t_tuning.decode_workers + 3) / 4 * 4 : 2 * compute_units() * 4;
 }
 struct StreamKPlan {
   bool use;
@@ -87,7 +107,7 @@ struct StreamKPlan {
 };
 StreamKPlan plan_streamk(const diffqkv_shape* s, int32_t max_T) {
   StreamKPlan k = {};
-  if (g_tuning.decode_ragged_mode == 2 || s->dtype != DIFFQKV_BF16 || s->B <= 0 || max_T <= 0) return k;
+  if (t_tuning.decode_ragged_mode == 2 || s->dtype != DIFFQKV_BF16 || s->B <= 0 || max_T <= 0) return k;
   if (s->B > decode_streamk_max_batch()) return k;
   int32_t chunk, splits;
   plan_decode(s, max_T, true, &chunk, &splits);
@@ -114,10 +134,10 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
   p.n_groups = s->n_k < s->n_v ? s->n_k : s->n_v;
   p.G = s->n_q / p.n_groups;
   p.scale_log2 = scale_log2(s);
-  const bool mfma = !g_tuning.force_generic && decode_mfma_supported(p, s->dtype);
+  const bool mfma = !t_tuning.force_generic && decode_mfma_supported(p, s->dtype);
   // ragged lengths on the MFMA kernel: equal slices per wavefront instead of fixed chunks
   StreamKPlan sk = {};
-  if (mfma && (p.seqlens != nullptr || g_tuning.decode_ragged_mode == 1)) sk = plan_streamk(s, p.T);
+  if (mfma && (p.seqlens != nullptr || t_tuning.decode_ragged_mode == 1)) sk = plan_streamk(s, p.T);
   size_t need;
   if (sk.use) {
     p.chunk = 0;
@@ -147,7 +167,7 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
   else
     e = launch_decode_generic(p, s->dtype, paged, stream);
   if (e != hipSuccess) return DIFFQKV_ERR_HIP;
-  if (g_split_event && hipEventRecord(g_split_event, stream) != hipSuccess) return DIFFQKV_ERR_HIP;
+  if (t_split_event && hipEventRecord(t_split_event, stream) != hipSuccess) return DIFFQKV_ERR_HIP;
   if (p.num_splits > 1) {
     e = launch_combine(p, s->dtype, stream);
     if (e != hipSuccess) return DIFFQKV_ERR_HIP;
@@ -161,13 +181,12 @@ extern "C" {
 
 void diffqkv_set_tuning(const diffqkv_tuning* t) {
   if (t)
-    g_tuning = *t;
+    t_tuning = *t;
   else
-    memset(&g_tuning, 0, sizeof g_tuning);
-  set_prefill_waves(g_tuning.prefill_waves);
+    memset(&t_tuning, 0, sizeof t_tuning);
 }
 
-void diffqkv_set_split_event(void* hip_event) { g_split_event = (hipEvent_t)hip_event; }
+void diffqkv_set_split_event(void* hip_event) { t_split_event = (hipEvent_t)hip_event; }
 
 size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape, int32_t max_T) {
   if (check_shape(shape) != DIFFQKV_OK || max_T < 0) return 0;
@@ -268,7 +287,8 @@ size_t diffqkv_decode_topk_workspace_bytes(const diffqkv_shape* shape, int32_t m
 
 static int run_topk(const diffqkv_shape* shape, TopkParams& p, bool paged, int32_t top_k, int32_t renormalize,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (top_k < 0 || top_k > topk_max_k()) return DIFFQKV_ERR_SHAPE;
+  if (top_k < 0) return DIFFQKV_ERR_SHAPE;
+  if (top_k > topk_max_k()) return DIFFQKV_ERR_UNSUPPORTED;  // more rows than the select kernel keeps on chip
   const size_t need = diffqkv_decode_topk_workspace_bytes(shape, p.T);
   if (need) {
     if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
@@ -283,13 +303,13 @@ static int run_topk(const diffqkv_shape* shape, TopkParams& p, bool paged, int32
   p.d_v = shape->d_v;
   p.top_k = top_k;
   p.renormalize = renormalize ? 1 : 0;
-  p.chunk = g_tuning.decode_chunk_tokens > 0
-                ? (g_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum
+  p.chunk = t_tuning.decode_chunk_tokens > 0
+                ? (t_tuning.decode_chunk_tokens + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum
                 : 512;
   p.scale_log2 = scale_log2(shape);
   p.scores = (float*)workspace;
   if (shape->B == 0) return DIFFQKV_OK;
-  const bool mfma = !g_tuning.force_generic && topk_scores_mfma_supported(p, shape->dtype);
+  const bool mfma = !t_tuning.force_generic && topk_scores_mfma_supported(p, shape->dtype);
   return launch_topk(p, shape->dtype, paged, mfma, (hipStream_t)hip_stream) == hipSuccess ? DIFFQKV_OK
                                                                                              : DIFFQKV_ERR_HIP;
 }
@@ -475,8 +495,8 @@ int diffqkv_prefill(const diffqkv_shape* shape, const void* q, const void* k, co
   p.scale_log2 = scale_log2(shape);
   if (shape->B == 0) return DIFFQKV_OK;
   hipError_t e;
-  if (!g_tuning.force_generic && prefill_mfma_supported(p, shape->dtype))
-    e = launch_prefill_mfma(p, (hipStream_t)hip_stream);
+  if (!t_tuning.force_generic && prefill_mfma_supported(p, shape->dtype))
+    e = launch_prefill_mfma(p, t_tuning.prefill_waves, (hipStream_t)hip_stream);
   else
     e = launch_prefill_generic(p, shape->dtype, (hipStream_t)hip_stream);
   return e == hipSuccess ? DIFFQKV_OK : DIFFQKV_ERR_HIP;
@@ -486,7 +506,8 @@ static int check_augq(const diffqkv_augq_shape* s) {
   if (!s) return DIFFQKV_ERR_NULL;
   if (s->M < 0 || s->hidden <= 0 || s->inter <= 0 || s->hidden % 8 || s->inter % 8) return DIFFQKV_ERR_SHAPE;
   if (s->dtype != DIFFQKV_F32 && s->dtype != DIFFQKV_BF16) return DIFFQKV_ERR_SHAPE;
-  if ((int64_t)s->hidden * s->inter > (1ll << 40) || (int64_t)s->M * s->inter > (1ll << 40)) return DIFFQKV_ERR_SHAPE;
+  if ((int64_t)s->hidden * s->inter > (1ll << 40) || (int64_t)s->M * s->inter > (1ll << 40))
+    return DIFFQKV_ERR_UNSUPPORTED;  // valid, but beyond the index range the kernels are built for
   return DIFFQKV_OK;
 }
 
@@ -508,7 +529,7 @@ int diffqkv_augment_q(const diffqkv_augq_shape* shape, const void* q_in, const v
   const size_t need = diffqkv_augment_q_workspace_bytes(shape);
   if (!workspace || workspace_bytes < need) return DIFFQKV_ERR_WORKSPACE;
   if (!aligned16(workspace)) return DIFFQKV_ERR_ALIGN;
-  const bool mfma = !g_tuning.force_generic && augq_mfma_supported(shape->dtype, shape->hidden, shape->inter);
+  const bool mfma = !t_tuning.force_generic && augq_mfma_supported(shape->dtype, shape->hidden, shape->inter);
   AugqParams p = {};
   p.x = q_in;
   p.w0 = w_gate;
@@ -549,6 +570,6 @@ const char* diffqkv_strerror(int status) {
   }
 }
 
-int diffqkv_version(void) { return 100; }
+int diffqkv_version(void) { return 200; }
 
 }  // extern "C"

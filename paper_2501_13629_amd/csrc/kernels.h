@@ -89,10 +89,10 @@ hipError_t launch_decode_mfma(const DecodeParams& p, bool paged, hipStream_t s);
 hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t s);
 bool prefill_mfma_supported(const PrefillParams& p, int dtype);
-hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s);
+// variant: 0 choose; 8 / 4 wavefronts of 32 rows; 2 = the 64-row kernel where supported
+hipError_t launch_prefill_mfma(const PrefillParams& p, int variant, hipStream_t s);
 bool prefill_mfma64_supported(const PrefillParams& p, int dtype);       // d_qk = d_v = 128 only
 hipError_t launch_prefill_mfma64(const PrefillParams& p, hipStream_t s);  // 64 query rows per wavefront
-void set_prefill_waves(int nw);  // 0 choose; 8 / 4 wavefronts of 32 rows; 2 = the 64-row kernel where supported
 int topk_max_k();
 bool topk_scores_mfma_supported(const TopkParams& p, int dtype);
 hipError_t launch_topk(const TopkParams& p, int dtype, bool paged, bool mfma, hipStream_t s);

@@ -350,7 +350,6 @@ bool prefill_mfma_supported(const PrefillParams& p, int dtype) {
 }
 
 namespace {
-int g_prefill_waves = 0;  // 0: choose; 8: 8 wavefronts x 32 rows; 4: 4 x 32; 2: the 64-rows-per-wavefront kernel
 template <int DQK, int DV, int NW, int QB>
 hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
   constexpr int kBM = NW * 32 * QB;
@@ -361,22 +360,21 @@ hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
   prefill_mfma_kernel<DQK, DV, NW, QB><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
   return hipGetLastError();
 }
+// variant: 0 choose; 8 / 4 wavefronts of 32 rows; 2 = the 64-rows-per-wavefront kernel where supported
 template <int DQK, int DV>
-hipError_t launch_variant(const PrefillParams& p, hipStream_t s) {
-  if ((g_prefill_waves == 0 || g_prefill_waves == 2) && prefill_mfma64_supported(p, 1))
-    return launch_prefill_mfma64(p, s);
-  if (g_prefill_waves == 4) return launch_nw<DQK, DV, 4, 1>(p, s);
+hipError_t launch_variant(const PrefillParams& p, int variant, hipStream_t s) {
+  if ((variant == 0 || variant == 2) && prefill_mfma64_supported(p, 1)) return launch_prefill_mfma64(p, s);
+  if (variant == 4) return launch_nw<DQK, DV, 4, 1>(p, s);
   return launch_nw<DQK, DV, 8, 1>(p, s);
 }
 }  // namespace
 
-void set_prefill_waves(int nw) { g_prefill_waves = (nw == 2 || nw == 4 || nw == 8) ? nw : 0; }
-
-hipError_t launch_prefill_mfma(const PrefillParams& p, hipStream_t s) {
+hipError_t launch_prefill_mfma(const PrefillParams& p, int variant, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
-  if (p.d_qk == 128) return launch_variant<128, 128>(p, s);
-  if (p.d_v == 128) return launch_variant<64, 128>(p, s);
-  return launch_variant<64, 64>(p, s);
+  if (variant != 2 && variant != 4 && variant != 8) variant = 0;
+  if (p.d_qk == 128) return launch_variant<128, 128>(p, variant, s);
+  if (p.d_v == 128) return launch_variant<64, 128>(p, variant, s);
+  return launch_variant<64, 64>(p, variant, s);
 }
 
 }  // namespace diffqkv

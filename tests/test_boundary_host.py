@@ -11,7 +11,7 @@ from paper_2501_13629_amd.binding import Shape
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
-OK, E_NULL, E_SHAPE, E_HEADS, E_ALIGN, E_WS = 0, -1, -2, -3, -4, -5
+OK, E_NULL, E_SHAPE, E_HEADS, E_ALIGN, E_WS, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 
 
 @pytest.fixture(scope="module")
@@ -23,18 +23,21 @@ def lib():
     return binding.load_library()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "diffqkv.h")).read()
+def declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(diffqkv_[a-z_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
-    names = declared_functions()
-    assert len(names) >= 12
-    for name in names:
+    product, experimental = declared_functions("diffqkv.h"), declared_functions("diffqkv_experimental.h")
+    assert len(product) >= 12 and len(experimental) == 3
+    for name in product + experimental:
         assert hasattr(lib, name), name
-    assert set(names) == set(binding.EXPORTS)
+    assert set(product) == set(binding.EXPORTS)
+    assert set(experimental) == set(binding.EXPERIMENTAL_EXPORTS)
+    # the product header declares no knob and no measurement aid
+    assert not any(n in product for n in ("diffqkv_set_tuning", "diffqkv_set_split_event", "diffqkv_probe_stream_read"))
 
 
 def test_version_and_strerror(lib):
@@ -117,7 +120,7 @@ def test_topk_and_augmented_q_validation_codes(lib):
                                        top_k, 0, vp(0x4000), None, None, vp(ws), ws_bytes, None)
 
     assert topk(top_k=-1) == E_SHAPE
-    assert topk(top_k=513) == E_SHAPE  # more than the select kernel keeps in LDS
+    assert topk(top_k=513) == E_UNSUPPORTED  # valid, but more than the select kernel keeps in LDS
     assert topk(T=-1) == E_SHAPE
     assert topk(q=0) == E_NULL
     assert topk(q=0x1004) == E_ALIGN
@@ -138,6 +141,7 @@ def test_topk_and_augmented_q_validation_codes(lib):
     assert augq(A(4, 0, 96, 1)) == E_SHAPE
     assert augq(A(4, 60, 96, 1)) == E_SHAPE  # rows must be whole 16-byte pieces
     assert augq(A(4, 64, 96, 5)) == E_SHAPE
+    assert augq(A(4, 1 << 21, 1 << 21, 1)) == E_UNSUPPORTED  # a product of 2^42 weights
     assert augq(A(4, 64, 96, 1), q=0) == E_NULL
     assert augq(A(4, 64, 96, 1), wd=0x4008) == E_ALIGN
     assert augq(A(4, 64, 96, 1), ws=0) == E_WS
@@ -167,6 +171,39 @@ def test_split_plan_is_a_function_of_shapes(lib):
     binding.diffqkv_set_tuning()
     assert f == 8 * 32 * 16 * 129 * 4 and c == 8 * 32 * 64 * 129 * 4
     assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == a
+
+
+def test_knobs_are_per_thread_and_validation_runs_concurrently(lib):
+    """Two threads validate decode calls at the same time, each under its own experimental knobs: the
+    knobs of one thread never show in the other's split plan, and every call returns its own status."""
+    import threading
+
+    s = shape(B=8, n_q=32, n_k=2, n_v=8, d_qk=128, d_v=128)
+    default = lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768)
+    results, barrier = {}, threading.Barrier(2)
+
+    def worker(name, chunk, want_bytes):
+        binding.diffqkv_set_tuning(decode_chunk_tokens=chunk, decode_ragged_mode=2 if chunk else 0)
+        barrier.wait()
+        ok = True
+        for i in range(2000):
+            ok &= lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == want_bytes
+            ok &= decode(lib, shape(n_q=8, n_k=3)) == E_HEADS
+            ok &= decode(lib, shape(), T=-1) == E_SHAPE
+            ok &= decode(lib, shape(), k=0x2004) == E_ALIGN
+            ok &= decode(lib, shape(B=1), T=1 << 16, ws=0) == E_WS
+            ok &= decode(lib, shape(B=0), q=0, k=0, v=0, out=0, ws=0, ws_bytes=0) == OK
+        results[name] = ok
+        binding.diffqkv_set_tuning()
+
+    threads = [threading.Thread(target=worker, args=("chunk512", 512, 8 * 32 * 64 * 129 * 4)),
+               threading.Thread(target=worker, args=("default", 0, default))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert results == {"chunk512": True, "default": True}
+    assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == default  # this thread never set a knob
 
 
 def test_binding_refuses_cpu_tensors():

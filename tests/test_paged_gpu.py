@@ -1,5 +1,4 @@
 """GPU parity: diffqkv_decode_paged against the float64 oracle."""
-import numpy as np
 import pytest
 import torch
 
@@ -78,18 +77,13 @@ def test_poisoned_page_tails_and_unused_pages():
 
 
 def test_config4_ragged_paged_full():
-    """The full ragged workload in the default launch configuration; the oracle evaluates a sample
-    of the sequences (shortest, longest and a seeded draw) one by one against the same pool."""
+    """The full ragged workload in the default launch configuration (the one bench.py times): every one
+    of the 64 sequences is compared with the oracle, element by element, against the same pool."""
     cfg = inputs.config("paged_ragged")
     d = inputs.make_paged(cfg)
     out, lse = gpu_paged(d)
     torch.cuda.synchronize()
-    sl = d["seqlens"].numpy()
-    rng = np.random.default_rng(4)
-    rows = sorted(set([int(sl.argmin()), int(sl.argmax())] + list(rng.choice(len(sl), 6, replace=False))))
-    ref, ref_lse = oracle_paged(d, rows)
-    util.check(out[rows], ref, "bf16", "rows %s" % rows)
-    util.check_lse(lse[rows], ref_lse)
-    # properties that hold for every row: finite, and inside the convex hull bound of |V|
-    assert torch.isfinite(out.float()).all()
-    assert float(out.float().abs().max()) <= float(util.dev(d["v_pool"]).float().abs().max())
+    ref, ref_lse = oracle_paged(d)
+    assert ref.shape[0] == cfg["B"] == 64
+    util.check(out, ref, "bf16", "all %d sequences" % cfg["B"])
+    util.check_lse(lse, ref_lse)

@@ -115,10 +115,7 @@ def test_last_row_equals_decode():
 
 
 def test_config5_prefill_8k_full():
-    """Full-size causal prefill in the default launch configuration; the oracle evaluates sampled
-    query rows (first, last, tile boundaries and a seeded draw) for every head."""
+    """Full-size causal prefill in the default launch configuration (the one bench.py times): every
+    query row of every head of both sequences is compared with the oracle, element by element."""
     cfg = inputs.config("prefill_8k")
-    rng = np.random.default_rng(5)
-    rows = sorted(set([0, 1, 63, 64, 127, 128, 129, 255, 256, 4095, 4096, 8190, 8191] +
-                      [int(x) for x in rng.integers(0, 8192, 19)]))
-    run(cfg, rows=np.array(rows, dtype=np.int32))
+    run(cfg)

@@ -142,17 +142,19 @@ def test_paged(page_size):
     vc = brute.gather_paged(inputs.as_numpy(d["v_pool"]), d["block_table"].numpy(), sl, 2304)
     ref, _, ref_sel = oracle.decode_topk(inputs.as_numpy(d["q"]), kc, vc, 100, seqlens=sl)
     util.check(out, ref, "bf16")
-    for g, r in zip(sel.cpu().numpy().reshape(-1, 101), ref_sel.reshape(-1, 101)):
-        assert len(set(g[g >= 0])) == len(set(r[r >= 0]))
+    contiguous = {"q": d["q"], "k": torch.from_numpy(kc.view(np.int16)).view(torch.bfloat16)}
+    check_selection(sel.cpu().numpy(), ref_sel, contiguous, sl, oracle.default_scale(cfg["d_qk"]))
 
 
-def test_config3_shape_top100_sampled():
-    """Full 32k-context workload, top-100: the oracle checks two of the eight sequences."""
+def test_config3_shape_top100_full():
+    """Full 32k-context workload, top-100: all eight sequences against the oracle, outputs and selections."""
     cfg = inputs.config("decode_32k")
     d = inputs.make_decode(cfg)
-    out = binding.diffqkv_decode_topk(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]), 100)
+    out, lse, sel = binding.diffqkv_decode_topk(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]), 100,
+                                                want_lse=True, want_selection=True)
     torch.cuda.synchronize()
-    for b in (0, 7):
-        ref, _, _ = oracle.decode_topk(inputs.as_numpy(d["q"][b:b + 1]), inputs.as_numpy(d["k"][b:b + 1]),
-                                       inputs.as_numpy(d["v"][b:b + 1]), 100)
-        util.check(out[b:b + 1], ref, "bf16", "sequence %d" % b)
+    ref, ref_lse, ref_sel = oracle.decode_topk(inputs.as_numpy(d["q"]), inputs.as_numpy(d["k"]),
+                                               inputs.as_numpy(d["v"]), 100)
+    util.check(out, ref, "bf16", "all %d sequences" % cfg["B"])
+    util.check_lse(lse, ref_lse)
+    check_selection(sel.cpu().numpy(), ref_sel, d, np.full(cfg["B"], cfg["T"]), oracle.default_scale(cfg["d_qk"]))
