@@ -31,12 +31,19 @@ typedef struct {
 void diffqkv_set_tuning(const diffqkv_tuning* t /* host; NULL resets */);
 
 /*
- * When `hip_event` (a hipEvent_t passed as void*) is not NULL, every later decode call of this
- * thread records it on its stream between the split kernel and the combine kernel, so a caller that
- * brackets the call with two events of its own can time the two kernels separately.  NULL turns it
- * off.
+ * Kernel timer.  While it is on, the main kernel of every call of this thread (the split kernel of a
+ * decode call, the prefill kernel, the score kernel of a top-k call, the first product of the
+ * augmented-Q call) and the kernel that follows it (combine, select, second product) are launched with
+ * a pair of HIP events attached to their own dispatch, so that the pair reads that kernel's duration
+ * and nothing else.  diffqkv_kernel_timer_read waits for every timed launch of this thread since the
+ * last read and returns the average duration of the main kernel and of the second kernel in
+ * microseconds (0 where none was launched) and the number of main-kernel launches; any pointer may
+ * be NULL.  Both return a diffqkv_status.  Timed launches create HIP events, which are pooled and live
+ * until the process ends: switch the timer on for measurements only.
  */
-void diffqkv_set_split_event(void* hip_event);
+int diffqkv_kernel_timer(int on);
+int diffqkv_kernel_timer_read(float* main_us /* host */, float* second_us /* host */,
+                              int32_t* main_launches /* host */);
 
 /*
  * Reads `bytes` (a multiple of 16) from `src` (device) with 128-bit loads, as fast as the memory

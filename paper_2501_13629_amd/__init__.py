@@ -17,7 +17,8 @@ from .binding import (  # noqa: F401
     diffqkv_decode_workspace_bytes,
     diffqkv_prefill,
     diffqkv_probe_stream_read,
-    diffqkv_set_split_event,
+    diffqkv_kernel_timer,
+    diffqkv_kernel_timer_read,
     diffqkv_set_tuning,
     diffqkv_version,
     load_library,

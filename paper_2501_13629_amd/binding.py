@@ -28,7 +28,8 @@ EXPORTS = (
     "diffqkv_augment_q_workspace_bytes", "diffqkv_augment_q",
 )
 # include/diffqkv_experimental.h (knobs and measurement aids; per calling thread)
-EXPERIMENTAL_EXPORTS = ("diffqkv_set_tuning", "diffqkv_set_split_event", "diffqkv_probe_stream_read")
+EXPERIMENTAL_EXPORTS = ("diffqkv_set_tuning", "diffqkv_kernel_timer", "diffqkv_kernel_timer_read",
+                        "diffqkv_probe_stream_read")
 
 
 class Shape(ctypes.Structure):
@@ -102,8 +103,11 @@ def load_library() -> ctypes.CDLL:
     lib.diffqkv_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.diffqkv_strerror.restype = ctypes.c_char_p
     lib.diffqkv_strerror.argtypes = [ctypes.c_int]
-    lib.diffqkv_set_split_event.restype = None
-    lib.diffqkv_set_split_event.argtypes = [vp]
+    lib.diffqkv_kernel_timer.restype = ctypes.c_int
+    lib.diffqkv_kernel_timer.argtypes = [ctypes.c_int]
+    lib.diffqkv_kernel_timer_read.restype = ctypes.c_int
+    lib.diffqkv_kernel_timer_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
+                                              ctypes.POINTER(ctypes.c_int32)]
     lib.diffqkv_version.restype = ctypes.c_int
     lib.diffqkv_version.argtypes = []
     _lib = lib
@@ -148,10 +152,17 @@ def diffqkv_set_tuning(decode_chunk_tokens: int = 0, force_generic: bool = False
     load_library().diffqkv_set_tuning(ctypes.byref(t))
 
 
-def diffqkv_set_split_event(event) -> None:
-    """`event`: a recorded-at-least-once torch.cuda.Event(enable_timing=True), or None to turn off."""
-    handle = None if event is None else ctypes.c_void_p(event.cuda_event)
-    load_library().diffqkv_set_split_event(handle)
+def diffqkv_kernel_timer(on: bool) -> None:
+    """Switch the calling thread's kernel timer on or off (see include/diffqkv_experimental.h)."""
+    _check(load_library().diffqkv_kernel_timer(1 if on else 0))
+
+
+def diffqkv_kernel_timer_read():
+    """Wait for the timed launches since the last read; returns (average main-kernel us, average
+    second-kernel us, number of main-kernel launches)."""
+    a, b, n = ctypes.c_float(0.0), ctypes.c_float(0.0), ctypes.c_int32(0)
+    _check(load_library().diffqkv_kernel_timer_read(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)))
+    return float(a.value), float(b.value), int(n.value)
 
 
 def diffqkv_version() -> int:

@@ -16,7 +16,7 @@ namespace {
 // Experimental knobs are per thread: they change only the calls of the thread that set them, and the
 // product entry points share no mutable state between threads.
 thread_local diffqkv_tuning t_tuning = {};
-thread_local hipEvent_t t_split_event = nullptr;
+thread_local KernelTimer t_kernel_timer = {};
 
 // Compute units of the current device, read once per device.  Without a device (validation-only use
 // on a host without a GPU) the figure of the chip this library is built for stands in.
@@ -167,7 +167,6 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
   else
     e = launch_decode_generic(p, s->dtype, paged, stream);
   if (e != hipSuccess) return DIFFQKV_ERR_HIP;
-  if (t_split_event && hipEventRecord(t_split_event, stream) != hipSuccess) return DIFFQKV_ERR_HIP;
   if (p.num_splits > 1) {
     e = launch_combine(p, s->dtype, stream);
     if (e != hipSuccess) return DIFFQKV_ERR_HIP;
@@ -176,6 +175,27 @@ int run_decode(const diffqkv_shape* s, DecodeParams& p, bool paged, void* worksp
 }
 
 }  // namespace
+
+namespace diffqkv {
+KernelTimer& kernel_timer() { return t_kernel_timer; }
+bool KernelTimer::next(int which, hipEvent_t* a, hipEvent_t* b) {
+  hipEvent_t e[2];
+  for (int i = 0; i < 2; ++i) {
+    if (!pool.empty()) {
+      e[i] = pool.back();
+      pool.pop_back();
+    } else if (hipEventCreate(&e[i]) != hipSuccess) {
+      if (i == 1) pool.push_back(e[0]);
+      return false;
+    }
+  }
+  start[which].push_back(e[0]);
+  stop[which].push_back(e[1]);
+  *a = e[0];
+  *b = e[1];
+  return true;
+}
+}  // namespace diffqkv
 
 extern "C" {
 
@@ -186,7 +206,35 @@ void diffqkv_set_tuning(const diffqkv_tuning* t) {
     memset(&t_tuning, 0, sizeof t_tuning);
 }
 
-void diffqkv_set_split_event(void* hip_event) { t_split_event = (hipEvent_t)hip_event; }
+int diffqkv_kernel_timer(int on) {
+  KernelTimer& t = t_kernel_timer;
+  t.on = on != 0;
+  return DIFFQKV_OK;
+}
+
+int diffqkv_kernel_timer_read(float* main_us, float* second_us, int32_t* main_launches) {
+  KernelTimer& t = t_kernel_timer;
+  float* dst[2] = {main_us, second_us};
+  if (main_launches) *main_launches = (int32_t)t.start[0].size();
+  int rc = DIFFQKV_OK;
+  for (int w = 0; w < 2; ++w) {
+    double sum_ms = 0.0;
+    const size_t n = t.start[w].size();
+    for (size_t i = 0; i < n; ++i) {
+      float ms = 0.f;
+      if (hipEventSynchronize(t.stop[w][i]) != hipSuccess ||
+          hipEventElapsedTime(&ms, t.start[w][i], t.stop[w][i]) != hipSuccess)
+        rc = DIFFQKV_ERR_HIP;
+      sum_ms += ms;
+      t.pool.push_back(t.start[w][i]);
+      t.pool.push_back(t.stop[w][i]);
+    }
+    t.start[w].clear();
+    t.stop[w].clear();
+    if (dst[w]) *dst[w] = n ? (float)(sum_ms * 1e3 / (double)n) : 0.f;
+  }
+  return rc;
+}
 
 size_t diffqkv_decode_workspace_bytes(const diffqkv_shape* shape, int32_t max_T) {
   if (check_shape(shape) != DIFFQKV_OK || max_T < 0) return 0;

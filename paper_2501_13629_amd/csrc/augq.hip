@@ -121,11 +121,11 @@ hipError_t launch_augq(const AugqParams& p, int dtype, bool gated, bool mfma, hi
     dim3 grid(p.N / 16, (p.M + 15) / 16);
     const bool six = batch_for(p.K) == 6;
     if (gated) {
-      if (six) augq_mfma_kernel<true, 6><<<grid, kWavesMfma * 64, 0, s>>>(p);
-      else augq_mfma_kernel<true, 4><<<grid, kWavesMfma * 64, 0, s>>>(p);
+      if (six) launch_kernel(0, augq_mfma_kernel<true, 6>, dim3(grid), dim3(kWavesMfma * 64), 0, s, p);
+      else launch_kernel(0, augq_mfma_kernel<true, 4>, dim3(grid), dim3(kWavesMfma * 64), 0, s, p);
     } else {
-      if (six) augq_mfma_kernel<false, 6><<<grid, kWavesMfma * 64, 0, s>>>(p);
-      else augq_mfma_kernel<false, 4><<<grid, kWavesMfma * 64, 0, s>>>(p);
+      if (six) launch_kernel(1, augq_mfma_kernel<false, 6>, dim3(grid), dim3(kWavesMfma * 64), 0, s, p);
+      else launch_kernel(1, augq_mfma_kernel<false, 4>, dim3(grid), dim3(kWavesMfma * 64), 0, s, p);
     }
   } else {
     dim3 grid((p.N + 3) / 4, p.M);

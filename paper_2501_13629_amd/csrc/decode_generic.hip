@@ -284,9 +284,9 @@ hipError_t launch_combine(const DecodeParams& p, int dtype, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
   dim3 grid(p.n_q, p.B), block(kCombineThreads);
   if (dtype == 0)
-    combine_kernel<float><<<grid, block, 0, s>>>(p);
+    launch_kernel(1, combine_kernel<float>, grid, block, 0, s, p);
   else
-    combine_kernel<uint16_t><<<grid, block, 0, s>>>(p);
+    launch_kernel(1, combine_kernel<uint16_t>, grid, block, 0, s, p);
   return hipGetLastError();
 }
 

@@ -511,15 +511,15 @@ hipError_t launch_ratio(const DecodeParams& p, bool paged, hipStream_t s) {
   if (p.sk_cum) {  // equal slices of the ragged unit space, one per wavefront
     dim3 grid(p.sk_workers / kWaves);
     if (paged)
-      decode_mfma_kernel<DQK, DV, true, RT, true><<<grid, block, 0, s>>>(p);
+      launch_kernel(0, decode_mfma_kernel<DQK, DV, true, RT, true>, grid, block, 0, s, p);
     else
-      decode_mfma_kernel<DQK, DV, false, RT, true><<<grid, block, 0, s>>>(p);
+      launch_kernel(0, decode_mfma_kernel<DQK, DV, false, RT, true>, grid, block, 0, s, p);
   } else {
     dim3 grid(p.num_splits, p.n_k, p.B);
     if (paged)
-      decode_mfma_kernel<DQK, DV, true, RT, false><<<grid, block, 0, s>>>(p);
+      launch_kernel(0, decode_mfma_kernel<DQK, DV, true, RT, false>, grid, block, 0, s, p);
     else
-      decode_mfma_kernel<DQK, DV, false, RT, false><<<grid, block, 0, s>>>(p);
+      launch_kernel(0, decode_mfma_kernel<DQK, DV, false, RT, false>, grid, block, 0, s, p);
   }
   return hipGetLastError();
 }

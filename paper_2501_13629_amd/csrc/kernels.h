@@ -1,7 +1,10 @@
 // Internal declarations shared by the translation units of libdiffqkv (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
+
+#include <vector>
 
 namespace diffqkv {
 
@@ -110,6 +113,29 @@ struct AugqParams {
 bool augq_mfma_supported(int dtype, int hidden, int inter);
 hipError_t launch_augq(const AugqParams& p, int dtype, bool gated, bool mfma, hipStream_t s);
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
+
+// ---- kernel timer (measurement aid of the experimental interface) ---------------------------------
+// While the calling thread has the timer on, the main kernel of a call (which = 0: the decode split
+// kernel, the prefill kernel, the top-k score kernel, the first augmented-Q product) and the kernel
+// after it (which = 1: combine, select, second product) are launched with a pair of HIP events attached
+// to their own dispatch: the difference of the pair is that kernel's duration, without the packets an
+// event recorded around a launch adds.  Off (the normal state), a launch is the plain one.
+struct KernelTimer {
+  bool on;
+  // event pairs handed to timed launches since the last read, and a pool they are taken from
+  std::vector<hipEvent_t> start[2], stop[2], pool;
+  bool next(int which, hipEvent_t* a, hipEvent_t* b);  // false if an event cannot be created
+};
+KernelTimer& kernel_timer();  // per thread; lives in api.hip
+template <typename K, typename... A>
+inline void launch_kernel(int which, K kernel, dim3 grid, dim3 block, size_t smem, hipStream_t s, A... args) {
+  KernelTimer& t = kernel_timer();
+  hipEvent_t a, b;
+  if (t.on && t.next(which, &a, &b))
+    hipExtLaunchKernelGGL(kernel, grid, block, smem, s, a, b, 0, args...);
+  else
+    kernel<<<grid, block, smem, s>>>(args...);
+}
 
 // ---- small device helpers -------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {

@@ -357,7 +357,7 @@ hipError_t launch_nw(const PrefillParams& p, hipStream_t s) {
   const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
-  prefill_mfma_kernel<DQK, DV, NW, QB><<<dim3((unsigned)n_wg), dim3(NW * 64), 0, s>>>(p, n_qtiles, xcd_aware);
+  launch_kernel(0, prefill_mfma_kernel<DQK, DV, NW, QB>, dim3((unsigned)n_wg), dim3(NW * 64), 0, s, p, n_qtiles, xcd_aware);
   return hipGetLastError();
 }
 // variant: 0 choose; 8 / 4 wavefronts of 32 rows; 2 = the 64-rows-per-wavefront kernel where supported

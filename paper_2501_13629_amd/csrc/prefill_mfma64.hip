@@ -523,7 +523,7 @@ hipError_t launch64(const PrefillParams& p, hipStream_t s) {
   const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
-  prefill_mfma64_kernel<DQK, DV><<<dim3((unsigned)n_wg), dim3(256), 0, s>>>(p, n_qtiles, xcd_aware);
+  launch_kernel(0, prefill_mfma64_kernel<DQK, DV>, dim3((unsigned)n_wg), dim3(256), 0, s, p, n_qtiles, xcd_aware);
   return hipGetLastError();
 }
 

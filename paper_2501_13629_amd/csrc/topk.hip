@@ -589,11 +589,11 @@ hipError_t launch_topk(const TopkParams& p, int dtype, bool paged, bool mfma, hi
     if (mfma) {
       dim3 grid((p.T_pad + p.chunk - 1) / p.chunk, p.n_k, p.B);
       if (p.d_qk == 128) {
-        if (paged) topk_scores_mfma_kernel<128, true><<<grid, kThreads, 0, s>>>(p);
-        else topk_scores_mfma_kernel<128, false><<<grid, kThreads, 0, s>>>(p);
+        if (paged) launch_kernel(0, topk_scores_mfma_kernel<128, true>, dim3(grid), dim3(kThreads), 0, s, p);
+        else launch_kernel(0, topk_scores_mfma_kernel<128, false>, dim3(grid), dim3(kThreads), 0, s, p);
       } else {
-        if (paged) topk_scores_mfma_kernel<64, true><<<grid, kThreads, 0, s>>>(p);
-        else topk_scores_mfma_kernel<64, false><<<grid, kThreads, 0, s>>>(p);
+        if (paged) launch_kernel(0, topk_scores_mfma_kernel<64, true>, dim3(grid), dim3(kThreads), 0, s, p);
+        else launch_kernel(0, topk_scores_mfma_kernel<64, false>, dim3(grid), dim3(kThreads), 0, s, p);
       }
     } else {
       dim3 grid((p.T_pad + kThreads - 1) / kThreads, p.n_q, p.B);
@@ -610,11 +610,11 @@ hipError_t launch_topk(const TopkParams& p, int dtype, bool paged, bool mfma, hi
   }
   dim3 grid2(p.n_q, p.B);
   if (dtype == 0) {
-    if (paged) topk_select_kernel<float, true><<<grid2, kSelThreads, 0, s>>>(p);
-    else topk_select_kernel<float, false><<<grid2, kSelThreads, 0, s>>>(p);
+    if (paged) launch_kernel(1, topk_select_kernel<float, true>, dim3(grid2), dim3(kSelThreads), 0, s, p);
+    else launch_kernel(1, topk_select_kernel<float, false>, dim3(grid2), dim3(kSelThreads), 0, s, p);
   } else {
-    if (paged) topk_select_kernel<uint16_t, true><<<grid2, kSelThreads, 0, s>>>(p);
-    else topk_select_kernel<uint16_t, false><<<grid2, kSelThreads, 0, s>>>(p);
+    if (paged) launch_kernel(1, topk_select_kernel<uint16_t, true>, dim3(grid2), dim3(kSelThreads), 0, s, p);
+    else launch_kernel(1, topk_select_kernel<uint16_t, false>, dim3(grid2), dim3(kSelThreads), 0, s, p);
   }
   return hipGetLastError();
 }

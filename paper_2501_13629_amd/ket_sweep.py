@@ -7,7 +7,8 @@ The paper's kernel-execution-time experiment (section 3.3, "KET Results"; append
 Efficiency Results") times its split and combine kernels on the trained model with n_q = 32,
 n_v = 16, head width 64, for n_k = 4 (Sigma) and n_k = 16 (Std), over prefix lengths 2k-32k.  The
 weights are not needed to time attention: this re-runs the same shapes on seeded random tensors and
-reports, per prefix length, the split and combine kernel times (HIP events on the launch stream) and
+reports, per prefix length, the average split and combine kernel times (HIP events attached to each
+dispatch: the library's experimental kernel timer) and
 the relative saving, next to the cost model's limit (32 - 20) / 32 = 37.5 % (section 3.2).
 """
 import argparse
@@ -35,18 +36,13 @@ def time_decode(cfg, steps=60, sets=4):
     for i in range(5):
         binding.diffqkv_decode(q, *caches[i % sets], out=out, workspace=ws)
     torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(steps)] for _ in range(3)]
+    binding.diffqkv_kernel_timer(True)
     for i in range(steps):
-        ev[1][i].record()
-        binding.diffqkv_set_split_event(ev[1][i])
-        ev[0][i].record()
         binding.diffqkv_decode(q, *caches[i % sets], out=out, workspace=ws)
-        ev[2][i].record()
-    binding.diffqkv_set_split_event(None)
     torch.cuda.synchronize()
-    split = sorted(ev[0][i].elapsed_time(ev[1][i]) * 1e3 for i in range(steps))
-    comb = sorted(ev[1][i].elapsed_time(ev[2][i]) * 1e3 for i in range(steps))
-    return split[steps // 2], comb[steps // 2], kv_bytes
+    split, comb, _ = binding.diffqkv_kernel_timer_read()
+    binding.diffqkv_kernel_timer(False)
+    return split, comb, kv_bytes
 
 
 def main():
