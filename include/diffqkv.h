@@ -60,7 +60,9 @@ typedef enum {
   DIFFQKV_ERR_WORKSPACE = -5,   /* workspace is NULL or smaller than the *_workspace_bytes figure  */
   DIFFQKV_ERR_UNSUPPORTED = -6, /* valid arguments this build has no kernel for (top_k above 512,
                                    an augmented-Q product beyond 2^40 elements)                    */
-  DIFFQKV_ERR_HIP = -7          /* a HIP call failed at launch time                                */
+  DIFFQKV_ERR_HIP = -7,         /* a HIP call failed at launch time                                */
+  DIFFQKV_ERR_STATIC_LIMIT = -8 /* diffqkv_decode_static: the call needs more scratch memory than
+                                   DIFFQKV_STATIC_SCRATCH_BYTES                                    */
 } diffqkv_status;
 
 /* Problem shape shared by all calls.  Supported head widths: multiples of 8 up to 256 (the tuned
@@ -99,6 +101,31 @@ int diffqkv_decode(const diffqkv_shape* shape /* host */, const void* q, const v
                    int64_t v_stride_b, int64_t v_stride_h, int64_t v_stride_t,
                    const int32_t* seqlens, int32_t T, void* out, float* lse_out, void* workspace,
                    size_t workspace_bytes, void* hip_stream);
+
+/*
+ * diffqkv_decode for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same kernels
+ * and bit-identical results as diffqkv_decode, minus the workspace: the partial results of the
+ * context splits go to a buffer of DIFFQKV_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing.
+ *
+ *   - A call whose diffqkv_decode_workspace_bytes(shape, T) exceeds DIFFQKV_STATIC_SCRATCH_BYTES
+ *     returns DIFFQKV_ERR_STATIC_LIMIT and enqueues nothing (32 MiB covers e.g. B = 8, n_q = 32,
+ *     d_v = 128 at T = 32768 with or without seqlens: 2.1 MB / 17.0 MB).
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress, which may load
+ *     the library's device image): make that first call outside any stream capture.
+ *   - All calls on one GPU share that GPU's buffer.  Nothing in it has to start at zero and a call
+ *     leaves nothing behind that a later call depends on, but two calls that overlap in time on one
+ *     GPU (different streams, different threads) race on it: keep them on one stream or serialise
+ *     them.  diffqkv_decode with separate workspaces has no such limit.
+ */
+#define DIFFQKV_STATIC_SCRATCH_BYTES (32u << 20)
+int diffqkv_decode_static(const diffqkv_shape* shape /* host */, const void* q, const void* k_cache,
+                          const void* v_cache, int64_t k_stride_b, int64_t k_stride_h,
+                          int64_t k_stride_t, int64_t v_stride_b, int64_t v_stride_h,
+                          int64_t v_stride_t, const int32_t* seqlens, int32_t T, void* out,
+                          float* lse_out, void* hip_stream);
 
 /*
  * Split decode over a paged cache (the paper only cites paged attention; the layout is this

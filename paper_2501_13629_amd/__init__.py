@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     diffqkv_append_paged,
     diffqkv_decode,
     diffqkv_decode_paged,
+    diffqkv_decode_static,
     diffqkv_decode_topk,
     diffqkv_decode_topk_paged,
     diffqkv_decode_workspace_bytes,

@@ -21,7 +21,7 @@ F32, BF16 = 0, 1
 
 # include/diffqkv.h
 EXPORTS = (
-    "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_paged",
+    "diffqkv_decode_workspace_bytes", "diffqkv_decode", "diffqkv_decode_static", "diffqkv_decode_paged",
     "diffqkv_prefill_workspace_bytes", "diffqkv_prefill", "diffqkv_strerror",
     "diffqkv_version", "diffqkv_append", "diffqkv_append_paged",
     "diffqkv_decode_topk_workspace_bytes", "diffqkv_decode_topk", "diffqkv_decode_topk_paged",
@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.diffqkv_decode_workspace_bytes.argtypes = [sp, i32]
     lib.diffqkv_decode.restype = ctypes.c_int
     lib.diffqkv_decode.argtypes = [sp, vp, vp, vp] + [i64] * 6 + [vp, i32, vp, vp, vp, sz, vp]
+    lib.diffqkv_decode_static.restype = ctypes.c_int
+    lib.diffqkv_decode_static.argtypes = [sp, vp, vp, vp] + [i64] * 6 + [vp, i32, vp, vp, vp]
     lib.diffqkv_decode_paged.restype = ctypes.c_int
     lib.diffqkv_decode_paged.argtypes = [sp, vp, vp, vp] + [i64] * 6 + [vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.diffqkv_prefill_workspace_bytes.restype = sz
@@ -219,6 +221,39 @@ def diffqkv_decode(q, k_cache, v_cache, seqlens=None, T=None, scale=None, out=No
         ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
         _ptr(seqlens), int(T), _ptr(out), _ptr(lse_out), _ptr(workspace), workspace.numel(), _stream(q)))
     return (out, lse_out) if (want_lse or lse_out is not None) else out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20  # DIFFQKV_STATIC_SCRATCH_BYTES
+
+
+def diffqkv_decode_static(q, k_cache, v_cache, out, seqlens=None, T=None, scale=None, lse_out=None):
+    """diffqkv_decode without a workspace: the split partials go to the library's static device
+    buffer and the call allocates nothing -- so `out` (and `lse_out`, if wanted) come from the caller."""
+    _dev(q, k_cache, v_cache, seqlens, out, lse_out)
+    dt = _dtype_code(q)
+    if _dtype_code(k_cache) != dt or _dtype_code(v_cache) != dt or _dtype_code(out) != dt:
+        raise TypeError("q, k_cache, v_cache and out must share a dtype")
+    if not q.is_contiguous() or not out.is_contiguous():
+        raise ValueError("q and out must be contiguous")
+    B, n_q, d_qk = q.shape
+    _, n_k, T_cap, _ = k_cache.shape
+    _, n_v, _, d_v = v_cache.shape
+    if tuple(out.shape) != (B, n_q, d_v):
+        raise ValueError("out must be [B, n_q, d_v]")
+    if k_cache.stride(3) != 1 or v_cache.stride(3) != 1:
+        raise ValueError("the channel dimension of the caches must be contiguous")
+    if T is None:
+        T = T_cap
+    if T > T_cap:
+        raise ValueError("T exceeds the cache capacity")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or not seqlens.is_contiguous()):
+        raise TypeError("seqlens must be a contiguous int32 tensor")
+    s = _shape(B, n_q, n_k, n_v, d_qk, d_v, dt, scale)
+    ks, vs = k_cache.stride(), v_cache.stride()
+    _check(load_library().diffqkv_decode_static(
+        ctypes.byref(s), _ptr(q), _ptr(k_cache), _ptr(v_cache), ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
+        _ptr(seqlens), int(T), _ptr(out), _ptr(lse_out), _stream(q)))
+    return out
 
 
 def diffqkv_decode_paged(q, k_pool, v_pool, block_table, seqlens, scale=None, out=None, lse_out=None,

@@ -4,12 +4,19 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "../../include/diffqkv.h"
 #include "../../include/diffqkv_experimental.h"
 #include "kernels.h"
 
 using namespace diffqkv;
+
+// Scratch memory of diffqkv_decode_static: the partial results of the context splits live here instead
+// of in a caller's workspace, so that the call allocates nothing.  One copy per GPU, at an address of
+// its own on each; the name below is only a host-side handle for hipGetSymbolAddress, never an address
+// to hand to a kernel.
+static __device__ __align__(256) unsigned char scratch[DIFFQKV_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -32,6 +39,23 @@ int compute_units() {
     return kDefaultComputeUnits;
   g_compute_units[dev].store(cu, std::memory_order_relaxed);
   return cu;
+}
+
+// Device address of `scratch` on the current device, looked up on the first call there.
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(void** ptr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return DIFFQKV_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return DIFFQKV_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DIFFQKV_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return DIFFQKV_OK;
 }
 
 // Split plan, a pure function of the shapes and of the device's compute-unit count.  Measured on
@@ -282,6 +306,26 @@ int diffqkv_decode(const diffqkv_shape* shape, const void* q, const void* k_cach
   p.out = out;
   p.lse_out = lse_out;
   return run_decode(shape, p, false, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int diffqkv_decode_static(const diffqkv_shape* shape, const void* q, const void* k_cache,
+                          const void* v_cache, int64_t k_stride_b, int64_t k_stride_h, int64_t k_stride_t,
+                          int64_t v_stride_b, int64_t v_stride_h, int64_t v_stride_t,
+                          const int32_t* seqlens, int32_t T, void* out, float* lse_out, void* hip_stream) {
+  // sizes first: a call whose partial results do not fit the static buffer is refused outright
+  if (check_shape(shape) == DIFFQKV_OK && T >= 0 &&
+      diffqkv_decode_workspace_bytes(shape, T) > (size_t)DIFFQKV_STATIC_SCRATCH_BYTES)
+    return DIFFQKV_ERR_STATIC_LIMIT;
+  void* ptr = nullptr;
+  if (shape && shape->B > 0) {  // (the empty batch launches nothing and needs no device)
+    const int rc = static_scratch(&ptr);
+    if (rc != DIFFQKV_OK) return rc;
+  }
+  // Nothing in the buffer has to start at zero: a split's slot is written before the combine kernel
+  // reads it, and slots of splits past the end of a sequence are never read.
+  return diffqkv_decode(shape, q, k_cache, v_cache, k_stride_b, k_stride_h, k_stride_t, v_stride_b, v_stride_h,
+                        v_stride_t, seqlens, T, out, lse_out, ptr, ptr ? (size_t)DIFFQKV_STATIC_SCRATCH_BYTES : 0,
+                        hip_stream);
 }
 
 int diffqkv_decode_paged(const diffqkv_shape* shape, const void* q, const void* k_pool,
@@ -614,6 +658,7 @@ const char* diffqkv_strerror(int status) {
     case DIFFQKV_ERR_WORKSPACE: return "workspace missing or too small";
     case DIFFQKV_ERR_UNSUPPORTED: return "no kernel for these arguments";
     case DIFFQKV_ERR_HIP: return "HIP launch failed";
+    case DIFFQKV_ERR_STATIC_LIMIT: return "the call needs more scratch memory than the library's static buffer holds";
     default: return "unknown status";
   }
 }

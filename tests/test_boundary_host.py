@@ -43,7 +43,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.diffqkv_version() >= 100
     assert lib.diffqkv_strerror(0) == b"ok"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         assert len(lib.diffqkv_strerror(code)) > 3
 
 
@@ -204,6 +204,20 @@ def test_knobs_are_per_thread_and_validation_runs_concurrently(lib):
         t.join()
     assert results == {"chunk512": True, "default": True}
     assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) == default  # this thread never set a knob
+
+
+def test_static_decode_refuses_sizes_beyond_its_buffer(lib):
+    """The entry point that allocates nothing checks the size before it touches a device."""
+    s = shape(B=64, n_q=32, n_k=2, n_v=8, d_qk=128, d_v=128)
+    assert lib.diffqkv_decode_workspace_bytes(ctypes.byref(s), 32768) > binding.STATIC_SCRATCH_BYTES
+    vp = ctypes.c_void_p
+    rc = lib.diffqkv_decode_static(ctypes.byref(s), vp(0x1000), vp(0x2000), vp(0x3000), 1 << 23, 1 << 22, 128,
+                                   1 << 25, 1 << 22, 128, None, 32768, vp(0x4000), None, None)
+    assert rc == -8 and b"static" in lib.diffqkv_strerror(rc)
+    # an empty batch is a valid no-op here too
+    e = shape(B=0)
+    assert lib.diffqkv_decode_static(ctypes.byref(e), None, None, None, 64, 64, 64, 64, 64, 64, None, 16, None, None,
+                                     None) == OK
 
 
 def test_binding_refuses_cpu_tensors():
