@@ -584,6 +584,7 @@ int diffqkv_prefill(const diffqkv_shape* shape, const void* q, const void* k, co
   p.S_q = S_q;
   p.S_k = S_k;
   p.causal = causal ? 1 : 0;
+  p.n_cu = compute_units();
   p.scale_log2 = scale_log2(shape);
   if (shape->B == 0) return DIFFQKV_OK;
   hipError_t e;

@@ -43,6 +43,7 @@ struct PrefillParams {
   void* out;      // [B, n_q, S_q, d_v]
   float* lse_out; // [B, n_q, S_q] or nullptr
   int32_t B, n_q, n_k, n_v, d_qk, d_v, S_q, S_k, causal;
+  int32_t n_cu;  // compute units of the device (sizes the grid of the persistent kernel)
   float scale_log2;
 };
 

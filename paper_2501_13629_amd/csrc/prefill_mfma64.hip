@@ -7,6 +7,14 @@
 // feeds two matrix instructions -- half the LDS traffic per flop -- and the 64 x d_v output
 // accumulators live in the accumulation registers, which the matrix instructions address directly.
 //
+// The workgroups are persistent: one per compute unit, each walking through its share of the work,
+// which is dealt out in units of two query tiles of one (sequence, query head) -- tile k from the top
+// with tile k from the bottom, so that under the causal mask every unit has the same number of
+// K/V tile steps.  The K/V tiles of consecutive tiles of work form one continuous stream through
+// the three LDS buffers and the staging registers: while the last steps of one query tile run, the
+// first K/V tiles of the next are already being loaded and stored, and the next Q is loaded under the
+// output epilogue, so that only the very first tile of a workgroup pays the latency of a cold start.
+//
 // With a single wavefront per SIMD nothing but the instruction stream itself overlaps the vector
 // ALU (exponentials) with the matrix cores, so the loop is software-pipelined over 32-token blocks.
 // For tile t (blocks 0 and 1) a step runs four phases of 16 matrix instructions each:
@@ -84,10 +92,22 @@ struct Smem64 {
   static constexpr int kKPitch = DQK + 8;  // bf16 elements per K row (16 B of padding)
   uint16_t k[3][kBN][kKPitch];
   uint16_t vt[3][DV][kBN];
+  // one slice per wavefront through which a block of 32 output rows leaves (see the epilogue)
+  static constexpr int kOutPitch = DV * 2 + 8;  // bytes per row; the 8 spread the rows over the banks
+  char out[4][32 * kOutPitch];
+};
+
+// The work of a launch: units = pairs of query tiles (tile n-1-k and tile k of one (sequence, query
+// head)); workgroup w of G takes the units w, w + G, w + 2 G, ...
+struct Schedule64 {
+  int n_qtiles;   // query tiles of 256 rows per (sequence, query head)
+  int n_pairs;    // ceil(n_qtiles / 2)
+  int n_units;    // n_pairs * n_q * B
+  int xcd_aware;  // unit numbering that keeps the query heads of a K head on one XCD
 };
 
 template <int DQK, int DV>
-__global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p, int n_qtiles, int xcd_aware) {
+__global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p, Schedule64 sch) {
   static_assert(DQK == 128 && DV == 128, "the slot schedule below is laid out for four phases of eight fragments");
   constexpr int KS = DQK / 16;  // k-steps of the score product (16 channels each)
   constexpr int CB = DV / 32;   // 32-channel blocks of the output
@@ -98,39 +118,87 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5, n = lane & 31;
-
-  int b, h, qtile;
-  locate_block(p, blockIdx.x, n_qtiles, xcd_aware, b, h, qtile);
-  const int kh = (int)(((int64_t)h * p.n_k) / p.n_q), vh = (int)(((int64_t)h * p.n_v) / p.n_q);
   const int off = p.S_k - p.S_q;   // query i sees keys j <= i + off when causal
-  const int q0 = qtile * kBM;      // first query row of the workgroup
-  const int r0 = q0 + wave * 64;   // first query row of this wavefront
 
-  const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)b * p.n_q + h) * p.S_q * DQK;
-  const rsrc_t k_rsrc = make_rsrc((const uint16_t*)p.k + ((int64_t)b * p.n_k + kh) * p.S_k * DQK, p.S_k * DQK * 2);
-  const rsrc_t v_rsrc = make_rsrc((const uint16_t*)p.v + ((int64_t)b * p.n_v + vh) * p.S_k * DV, p.S_k * DV * 2);
-
-  // tokens this workgroup / this wavefront can see
-  int wg_limit = p.S_k, wave_limit = p.S_k;
-  if (p.causal) {
-    const int lastq = (q0 + kBM < p.S_q ? q0 + kBM : p.S_q) - 1;
-    wg_limit = lastq + off + 1;
-    int lastw = r0 + 63;
-    lastw = lastw < p.S_q ? lastw : p.S_q - 1;
-    wave_limit = lastw + off + 1;  // (<= 0 for a wavefront whose rows are all past S_q: it only stages)
-  }
-  const int n_tiles = (wg_limit + kBN - 1) / kBN;
+  // ---- the tiles of work of this workgroup, in order: seq = 2 * round + part -----------------------
+  // part 0 is the pair's tile from the bottom (the longer one under the causal mask), part 1 the
+  // tile from the top; a pair whose two tiles coincide (the middle one of an odd count) has no part 1.
+  struct Work {
+    int b, h, qtile;
+    int n_tiles;  // K/V tiles the workgroup walks through for it
+  };
+  const int n_seq = 2 * ((sch.n_units - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x);
+  auto work_at = [&](int seq, Work& w) -> bool {  // false: no such tile of work
+    if (seq >= n_seq) return false;
+    const int x = (seq >> 1) * (int)gridDim.x + (int)blockIdx.x;
+    int pair;
+    const int g_k = p.n_q / p.n_k;
+    if (sch.xcd_aware) {
+      const int groups_per_xcd = p.B * p.n_k / kXcds;
+      const int c = x % kXcds, j = x / kXcds;
+      const int hq = j % g_k, t = j / g_k;
+      const int group = (t % groups_per_xcd) * kXcds + c;
+      pair = t / groups_per_xcd;
+      w.b = group / p.n_k;
+      w.h = (group % p.n_k) * g_k + hq;
+    } else {
+      w.h = x % p.n_q;
+      w.b = (x / p.n_q) % p.B;
+      pair = x / (p.n_q * p.B);
+    }
+    const int bottom = sch.n_qtiles - 1 - pair;
+    if (seq & 1) {
+      if (bottom == pair) return false;
+      w.qtile = pair;
+    } else {
+      w.qtile = bottom;
+    }
+    int wg_limit = p.S_k;
+    if (p.causal) {
+      const int q0 = w.qtile * kBM;
+      const int lastq = (q0 + kBM < p.S_q ? q0 + kBM : p.S_q) - 1;
+      wg_limit = lastq + off + 1;
+    }
+    // (all of this is the same in every lane; saying so keeps it, and the buffer resources made from
+    //  it, in scalar registers)
+    w.n_tiles = __builtin_amdgcn_readfirstlane((wg_limit + kBN - 1) / kBN);
+    w.b = __builtin_amdgcn_readfirstlane(w.b);
+    w.h = __builtin_amdgcn_readfirstlane(w.h);
+    w.qtile = __builtin_amdgcn_readfirstlane(w.qtile);
+    return true;
+  };
+  auto next_work = [&](int seq, Work& w) -> int {  // the first tile of work after seq; n_seq if none
+    for (++seq; seq < n_seq; ++seq)
+      if (work_at(seq, w)) return seq;
+    return n_seq;
+  };
+  auto uniform = [](const uint16_t* ptr) {
+    const uint64_t a = (uint64_t)(uintptr_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return (const uint16_t*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+  };
+  auto k_head = [&](const Work& w) {
+    const int kh = (int)(((int64_t)w.h * p.n_k) / p.n_q);
+    return make_rsrc(uniform((const uint16_t*)p.k + ((int64_t)w.b * p.n_k + kh) * p.S_k * DQK), p.S_k * DQK * 2);
+  };
+  auto v_head = [&](const Work& w) {
+    const int vh = (int)(((int64_t)w.h * p.n_v) / p.n_q);
+    return make_rsrc(uniform((const uint16_t*)p.v + ((int64_t)w.b * p.n_v + vh) * p.S_k * DV), p.S_k * DV * 2);
+  };
 
   // ---- Q^T as the B operand: lane (half, n) holds channels 16 ks + 8 half .. + 7 of its two rows ----
   u32x4 qf[2][KS];
+  auto load_q = [&](const Work& w, u32x4 (&q)[2][KS]) {
+    const uint16_t* qbase = (const uint16_t*)p.q + ((int64_t)w.b * p.n_q + w.h) * p.S_q * DQK;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    int row = r0 + 32 * qb + n;
-    row = row < p.S_q ? row : p.S_q - 1;
-    const uint16_t* qrow = qbase + (int64_t)row * DQK + half * 8;
+    for (int qb = 0; qb < 2; ++qb) {
+      int row = w.qtile * kBM + wave * 64 + 32 * qb + n;
+      row = row < p.S_q ? row : p.S_q - 1;
+      const uint16_t* qrow = qbase + (int64_t)row * DQK + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const u32x4*)(qrow + ks * 16);
-  }
+      for (int ks = 0; ks < KS; ++ks) q[qb][ks] = *(const u32x4*)(qrow + ks * 16);
+    }
+  };
 
   // ---- global -> register -> LDS staging of one K/V tile (every thread takes part in both) ----------
   // K tile = 64 rows x d_qk channels: 16 threads share a row (16 bytes each) and take KLD rows next
@@ -151,24 +219,28 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   const int k_row = (tid >> 4) * KLD, k_chunk = tid & 15;
   const int k_voff = k_row * (DQK * 2) + k_chunk * 16;
   u32x4 kst[KLD], vst[4];
-  auto load_k_tile = [&](int t0) {
+  // (t0: first token of the tile inside the head that the resource describes)
+  auto load_k_tile = [&](rsrc_t k_rsrc, int t0) {
 #pragma unroll
     for (int i = 0; i < KLD; ++i)
       kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, k_voff + t0 * (DQK * 2) + i * (DQK * 2), 0, 0);
   };
-  auto load_v_tile = [&](int t0) {
+  auto load_v_tile = [&](rsrc_t v_rsrc, int t0) {
     if (v_role) {
 #pragma unroll
       for (int x = 0; x < 4; ++x)
         vst[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2) + t0 * (DV * 2), 0, 0);
     }
   };
-  auto load_tile = [&](int t0) {
-    load_k_tile(t0);
-    load_v_tile(t0);
-  };
-  auto store_k_item = [&](int i, int buf) {  // i in [0, KLD)
-    *(u32x4*)&sm.k[buf][k_row + i][k_chunk * 8] = kst[i];
+  // (LDS addresses as integers: a per-lane part that the step computes once from the buffer index --
+  //  folded into the immediates where that index is a constant -- plus an immediate)
+  constexpr uint32_t kKBuf = kBN * Smem64<DQK, DV>::kKPitch * 2;  // bytes of one K buffer
+  constexpr uint32_t kVBuf = DV * kBN * 2;                         // bytes of one V^T buffer
+  constexpr uint32_t kKRow = Smem64<DQK, DV>::kKPitch * 2;
+  const uint32_t k_base = (uint32_t)(uintptr_t)&sm.k[0][0][0];
+  const uint32_t k_st = k_base + (uint32_t)(k_row * kKRow + k_chunk * 16);
+  auto store_k_item = [&](int i, uint32_t k_st_buf) {  // i in [0, KLD); k_st_buf = k_st + buffer * kKBuf
+    *(lds_u32x4*)(k_st_buf + (uint32_t)(i * kKRow)) = kst[i];
   };
   // The V^T store of channel e of this thread's chunk goes to row 8 v_c8 + e, granule (pos >> 3) ^
   // swizzle(row) = (pos >> 3) ^ (v_c8 & 7) ^ e: a per-lane byte offset with e XORed into bits 4-6
@@ -178,55 +250,50 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   //  immediate field of an LDS instruction reaches 64 KiB from there, which covers all three buffers)
   const uint32_t vt_base = (uint32_t)(uintptr_t)&sm.vt[0][0][0];
   const uint32_t v_st = vt_base + (uint32_t)(v_c8 * 8 * (kBN * 2) + ((((v_pos >> 3) ^ v_c8) & 7) << 4) + (v_pos & 7) * 2);
-  auto store_v_item = [&](int e, int vbuf) {  // channel e in [0, 8) of this thread's chunk
+  auto store_v_item = [&](int e, uint32_t v_st_buf) {  // channel e in [0, 8) of this thread's chunk; v_st_buf = v_st + buffer * kVBuf
     if (v_role) {
       // word e/2, low or high half, from the 4 tokens
       const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
       u32x2 w;
       w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
       w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
-      *(lds_u32x2*)((v_st ^ (uint32_t)(e << 4)) + (uint32_t)((vbuf * DV + e) * (kBN * 2))) = w;
+      *(lds_u32x2*)((v_st_buf ^ (uint32_t)(e << 4)) + (uint32_t)(e * (kBN * 2))) = w;
     }
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) store_k_item(i, buf);
+    for (int i = 0; i < KLD; ++i) store_k_item(i, k_st + (uint32_t)buf * kKBuf);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) store_v_item(e, buf);
+    for (int e = 0; e < 8; ++e) store_v_item(e, v_st + (uint32_t)buf * kVBuf);
   };
 
-  // ---- state ----------------------------------------------------------------------------------------
+  // ---- state of the tile of work in hand ----------------------------------------------------------------
+  int r0 = 0;           // first query row of this wavefront
   f32x16 acc[2][CB];     // accumulation registers
   f32x16 s[2][2];        // [row block][token block] scores
   uint32_t pw[2][2][8];  // [row block][token block] weights, bf16 pairs, as the B operand wants them
   float m_run[2], l_run[2];
+  auto reset_state = [&]() {
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < 2; ++qb) {
+      // (what the last tile of work left in the score and weight registers of block 0 is dead: say so,
+      //  or the compiler keeps those registers alive through the epilogue and the next Q's arrival)
+      asm volatile("" : "=v"(s[qb][0]));
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+      for (int i = 0; i < 8; ++i) asm volatile("" : "=v"(pw[qb][0][i]));
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[qb][cb][r] = 0.f;
+      for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[qb][1][r] = -INFINITY;  // "previous tile": weights of zero
+        for (int r = 0; r < 16; ++r) acc[qb][cb][r] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) pw[qb][1][i] = 0u;
-    m_run[qb] = kMinRef;
-    l_run[qb] = 0.f;
-  }
-  settle_a<CB>(acc);
-
-  load_tile(0);
-  store_tile(0);
-  load_tile(kBN);  // staging registers always hold the tile after the one in LDS
-  // the first step runs the "previous tile" output product with weights of zero, from buffer 2: make
-  // what it multiplies finite
+      for (int r = 0; r < 16; ++r) s[qb][1][r] = -INFINITY;  // "previous tile": weights of zero
 #pragma unroll
-  for (int i = 0; i < DV * kBN * 2 / 16 / kThreads; ++i) ((u32x4*)&sm.vt[2][0][0])[i * kThreads + tid] = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));  // Q has arrived, and sits in accumulation registers
-  __syncthreads();
+      for (int i = 0; i < 8; ++i) pw[qb][1][i] = 0u;
+      m_run[qb] = kMinRef;
+      l_run[qb] = 0.f;
+    }
+    settle_a<CB>(acc);
+  };
 
   // Softmax without a running maximum on the hot path.  Scores stay unscaled; the scale (> 0) is
   // folded into the exponent: p = 2^(c s - m_ref).  The reference m_ref of a row only has to keep the
@@ -308,28 +375,40 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   uint32_t vt_lane[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) vt_lane[c] = vt_base + (uint32_t)(n * (kBN * 2) + (((vt_swizzle(n) ^ half) ^ (2 * c)) << 4));
-  auto vt_frag = [&](int vb, auto kqc, auto cbc) {  // (vb: a constant wherever the caller's is)
+  auto vt_frag = [&](const uint32_t (&vt_buf)[4], auto kqc, auto cbc) {  // vt_buf[c] = vt_lane[c] + buffer * kVBuf
     constexpr int kq = decltype(kqc)::value, cb = decltype(cbc)::value;
     constexpr int c = ((2 * kq) ^ (4 * (cb & 1))) / 2;
-    return *(const lds_u32x4*)(vt_lane[c] + (uint32_t)((vb * DV + 32 * cb) * (kBN * 2)));
+    return *(const lds_u32x4*)(vt_buf[c] + (uint32_t)(32 * cb * (kBN * 2)));
   };
+  const uint32_t k_lane = k_base + (uint32_t)(n * kKRow + 16 * half);  // this lane's K fragment of row block 0, k-step 0
 
   // One tile step; see the header for the phase order.  MASKED (compile time) adds the causal / length
   // select on the finished score blocks, the only place that looks at token positions.
   bool pending = false;  // the previous tile's second block still waits for its output product
-  // A step of a wavefront that is past its last row: it only helps staging.
-  auto staging_step = [&](int it, int cur) {
+  // A step of a wavefront that is past its last row: it only helps staging.  (ld_k, ld_v, ld_tok:
+  // where the K/V stream stands two tiles ahead -- the tile whose loads this step issues.)
+  auto staging_step = [&](int cur, rsrc_t ld_k, rsrc_t ld_v, int ld_tok) {
     const int next = cur == 2 ? 0 : cur + 1;
     store_tile(next);
-    load_tile(it * kBN + 2 * kBN);
+    load_k_tile(ld_k, ld_tok);
+    load_v_tile(ld_v, ld_tok);
     __syncthreads();
   };
   // curc = it % 3, the buffer of this step's tile: an int, or a std::integral_constant -- then every
   // LDS address of the step is a loop-invariant register plus an immediate.
-  auto tile_step = [&](int it, auto masked_tag, auto curc) {
+  auto tile_step = [&](int it, auto masked_tag, auto curc, rsrc_t ld_k, rsrc_t ld_v, int ld_tok) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int cur = buffer_index(curc), next = cur == 2 ? 0 : cur + 1, prev = cur == 0 ? 2 : cur - 1;
     const int t0 = it * kBN;
+    // the step's LDS bases (constants folded into the immediates in the copies with a constant index)
+    const uint32_t k_cur = k_lane + (uint32_t)cur * kKBuf;
+    const uint32_t k_st_next = k_st + (uint32_t)next * kKBuf, v_st_next = v_st + (uint32_t)next * kVBuf;
+    uint32_t vt_cur[4], vt_prev[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      vt_cur[c] = vt_lane[c] + (uint32_t)cur * kVBuf;
+      vt_prev[c] = vt_lane[c] + (uint32_t)prev * kVBuf;
+    }
     {
       // fragment order: K block 0 | V^T of the previous tile's block 1 | K block 1 | V^T block 0
       constexpr int G0 = KS, G1 = KS + 2 * CB, G2 = 2 * KS + 2 * CB, kFrags = 2 * KS + 4 * CB;
@@ -338,16 +417,16 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       auto fetch = [&](auto fc) {
         constexpr int f = decltype(fc)::value;
         if constexpr (f < G0) {
-          fr[f % kRing] = *(const u32x4*)&sm.k[cur][n][16 * f + 8 * half];
+          fr[f % kRing] = *(const lds_u32x4*)(k_cur + (uint32_t)(32 * f));
         } else if constexpr (f < G1) {
           constexpr int j = f - G0;
-          fr[f % kRing] = vt_frag(prev, std::integral_constant<int, 2 + j / CB>{}, std::integral_constant<int, j % CB>{});
+          fr[f % kRing] = vt_frag(vt_prev, std::integral_constant<int, 2 + j / CB>{}, std::integral_constant<int, j % CB>{});
         } else if constexpr (f < G2) {
           constexpr int ks = f - G1;
-          fr[f % kRing] = *(const u32x4*)&sm.k[cur][32 + n][16 * ks + 8 * half];
+          fr[f % kRing] = *(const lds_u32x4*)(k_cur + (uint32_t)(32 * kKRow + 32 * ks));
         } else {
           constexpr int j = f - G2;
-          fr[f % kRing] = vt_frag(cur, std::integral_constant<int, j / CB>{}, std::integral_constant<int, j % CB>{});
+          fr[f % kRing] = vt_frag(vt_cur, std::integral_constant<int, j / CB>{}, std::integral_constant<int, j % CB>{});
         }
       };
       static_for<0, kRing>(fetch);
@@ -383,12 +462,12 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       };
       auto stage_item = [&](auto ic) {
         constexpr int idx = decltype(ic)::value;
-        // (unconditional: past the last tile the stores park stale registers in a buffer nobody
-        //  reads, and the loads fall outside the buffer resource and return zeros)
-        if constexpr (idx < KLD) store_k_item(idx, next);
-        else if constexpr (idx < KLD + 8) store_v_item(idx - KLD, next);
-        else if constexpr (idx == KLD + 8) load_k_tile(t0 + 2 * kBN);
-        else load_v_tile(t0 + 2 * kBN);
+        // (unconditional: past the last tile of the last piece of work the stores park stale registers
+        //  in a buffer nobody reads, and the loads go to an empty buffer resource and return zeros)
+        if constexpr (idx < KLD) store_k_item(idx, k_st_next);
+        else if constexpr (idx < KLD + 8) store_v_item(idx - KLD, v_st_next);
+        else if constexpr (idx == KLD + 8) load_k_tile(ld_k, ld_tok);
+        else load_v_tile(ld_v, ld_tok);
       };
       auto slot = [&](auto gc) {
         constexpr int g = decltype(gc)::value;
@@ -438,6 +517,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   };
   // The block that is still in flight after the last step a wavefront computes.
   auto drain = [&](int vprev) {  // vprev: buffer of the last tile computed
+    uint32_t vt_last[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) vt_last[c] = vt_lane[c] + (uint32_t)vprev * kVBuf;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -445,7 +527,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     close_block(std::integral_constant<int, 1>{});
     static_for<0, 2 * CB>([&](auto jc) {
       constexpr int j = decltype(jc)::value, sh = (j / CB) * 4;
-      const u32x4 a = vt_frag(vprev, std::integral_constant<int, 2 + j / CB>{}, std::integral_constant<int, j % CB>{});
+      const u32x4 a = vt_frag(vt_last, std::integral_constant<int, 2 + j / CB>{}, std::integral_constant<int, j % CB>{});
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
         mfma_a(acc[qb][j % CB], a, u32x4{pw[qb][1][sh], pw[qb][1][sh + 1], pw[qb][1][sh + 2], pw[qb][1][sh + 3]});
@@ -453,77 +535,186 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     pending = false;
   };
 
-  // tiles wholly visible to every row of this wavefront need no mask; tiles past its last row are
-  // staging only -- the pending block is finished before the first of those overwrites its buffer
-  int n_plain = p.S_k / kBN;
-  if (p.causal) {
-    const int vis = (r0 + off + 1) / kBN;  // tiles entirely at or before the first row's limit
-    n_plain = vis < n_plain ? vis : n_plain;
-  }
-  n_plain = n_plain < n_tiles ? n_plain : n_tiles;
-  int n_compute = wave_limit > 0 ? (wave_limit + kBN - 1) / kBN : 0;
-  n_compute = n_compute < n_tiles ? n_compute : n_tiles;
-  n_plain = n_plain < n_compute ? n_plain : n_compute;
-  // The bulk of the steps -- unmasked, three at a time, one per buffer -- run with constant buffer
-  // indices; the one or two unmasked steps that may be left over share the body of the masked steps
-  // around the diagonal (its selects pass everything there), which takes the index as a value: one
-  // more copy of the step for them would cost more in instruction-cache misses than the selects do.
-  int it = 0;
-  for (; it + 3 <= n_plain; it += 3) {
-    tile_step(it, std::false_type{}, std::integral_constant<int, 0>{});
-    tile_step(it + 1, std::false_type{}, std::integral_constant<int, 1>{});
-    tile_step(it + 2, std::false_type{}, std::integral_constant<int, 2>{});
-  }
-  int cur = 0;  // it % 3
-  for (; it < n_compute; ++it, cur = cur == 2 ? 0 : cur + 1) tile_step(it, std::true_type{}, cur);
-  if (pending) drain(cur == 0 ? 2 : cur - 1);
-  for (; it < n_tiles; ++it, cur = cur == 2 ? 0 : cur + 1) staging_step(it, cur);  // (t0 >= wave_limit from here on)
-
   // ---- write this wavefront's rows.  Lane (half, n) holds row 32 qb + n in pieces of four channels
   //      (acc[qb][cb][r]: channel 32 cb + 8 (r/4) + 4 half + r%4); stored from there, one instruction
   //      would touch 32 rows.  So each row block passes through a slice of LDS that belongs to this
-  //      wavefront alone (inside the K buffers: every wavefront has left the step loop through its
-  //      last barrier, and what may still run elsewhere, the drain, reads V^T only) and leaves in 16-byte
-  //      pieces, 16 lanes to a row: whole 256-byte rows per store.  The LDS operations of one
-  //      wavefront execute in order, so the slice needs no barrier.
-  settle_a<CB>(acc);
-  constexpr int kOutPitch = DV * 2 + 8;  // bytes per row in the slice; the 8 spread the rows over the banks
-  static_assert(4 * 32 * kOutPitch <= (int)sizeof(sm.k), "four slices fit in the K buffers");
-  char* const slice = (char*)&sm.k[0][0][0] + wave * (32 * kOutPitch);
-  const int o_row = lane >> 4, o_chunk = lane & 15;
+  //      wavefront alone and leaves in 16-byte pieces, 16 lanes to a row: whole 256-byte rows per
+  //      store.  The LDS operations of one wavefront execute in order, so the slice needs no barrier.
+  auto write_rows = [&](const Work& w) {
+    settle_a<CB>(acc);
+    constexpr int kOutPitch = Smem64<DQK, DV>::kOutPitch;
+    char* const slice = &sm.out[wave][0];
+    const int o_row = lane >> 4, o_chunk = lane & 15;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int my_row = r0 + 32 * qb + n;
-    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);  // both halves hold the full row sum now
-    const float inv = 1.f / l;
+    for (int qb = 0; qb < 2; ++qb) {
+      const int my_row = r0 + 32 * qb + n;
+      const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);  // both halves hold the full row sum now
+      const float inv = 1.f / l;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+      for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 w;
-        w[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
-        w[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
-        *(u32x2*)(slice + n * kOutPitch + (32 * cb + 8 * q4 + 4 * half) * 2) = w;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 x;
+          x[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
+          x[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
+          *(u32x2*)(slice + n * kOutPitch + (32 * cb + 8 * q4 + 4 * half) * 2) = x;
+        }
+      if (my_row < p.S_q && half == 0 && p.lse_out)
+        p.lse_out[((int64_t)w.b * p.n_q + w.h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
+      uint16_t* const oblock = (uint16_t*)p.out + (((int64_t)w.b * p.n_q + w.h) * p.S_q + r0 + 32 * qb) * DV;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = 4 * i + o_row;
+        const u32x4 piece = *(const u32x4*)(slice + row * kOutPitch + o_chunk * 16);
+        if (r0 + 32 * qb + row < p.S_q) *(u32x4*)(oblock + row * DV + o_chunk * 8) = piece;
       }
-    if (my_row < p.S_q && half == 0 && p.lse_out)
-      p.lse_out[((int64_t)b * p.n_q + h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
-    uint16_t* const oblock = (uint16_t*)p.out + (((int64_t)b * p.n_q + h) * p.S_q + r0 + 32 * qb) * DV;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = 4 * i + o_row;
-      const u32x4 piece = *(const u32x4*)(slice + row * kOutPitch + o_chunk * 16);
-      if (r0 + 32 * qb + row < p.S_q) *(u32x4*)(oblock + row * DV + o_chunk * 8) = piece;
     }
+  };
+
+  // ---- the K/V stream -------------------------------------------------------------------------------
+  // The K/V tiles of this workgroup's tiles of work, laid end to end, form one stream; every tile of
+  // work is padded to a multiple of three slots, so that each starts in LDS buffer 0 (the padding slots
+  // cost a barrier and a round of staging stores each, no arithmetic).  At the start of the step that
+  // takes stream slot g, LDS buffer g % 3 holds it, the staging registers hold slot g + 1 (stored into
+  // buffer (g + 1) % 3 during the step) and the step issues the loads of slot g + 2.  The cursor below
+  // is that slot g + 2: a head's buffer resources and a tile index inside the head.  On a padding slot,
+  // and past the last tile of work, it points at an empty resource (loads return zeros).
+  int ld_seq = -1, ld_tile = 0, ld_tiles = 0, ld_slots = 0;  // cursor: slot ld_tile of ld_slots, of which ld_tiles are tiles
+  rsrc_t ld_k = make_rsrc(p.k, 0), ld_v = make_rsrc(p.v, 0);
+  auto cursor_next_work = [&]() {
+    Work ld_work;
+    ld_seq = next_work(ld_seq, ld_work);
+    ld_tile = 0;
+    if (ld_seq < n_seq) {
+      ld_tiles = ld_work.n_tiles;
+      ld_slots = (ld_tiles + 2) / 3 * 3;
+      ld_k = k_head(ld_work);
+      ld_v = v_head(ld_work);
+    } else {
+      ld_tiles = ld_slots = 0x7ffffff0;
+      ld_k = make_rsrc(p.k, 0);
+      ld_v = make_rsrc(p.v, 0);
+    }
+  };
+  auto cursor_advance = [&](int slots) {  // (never across more than one boundary)
+    ld_tile += slots;
+    if (ld_tile >= ld_slots) {
+      cursor_next_work();
+    } else if (ld_tile >= ld_tiles) {  // padding
+      ld_k = make_rsrc(p.k, 0);
+      ld_v = make_rsrc(p.v, 0);
+    }
+  };
+
+  Work work;
+  int seq = next_work(-1, work);
+  if (seq >= n_seq) return;  // (a workgroup without work: the grid is never larger than the unit count)
+  // cold start: Q and the first two tiles of the stream
+  load_q(work, qf);
+  cursor_next_work();  // -> tile 0 of the first tile of work
+  load_k_tile(ld_k, ld_tile * kBN);
+  load_v_tile(ld_v, ld_tile * kBN);
+  cursor_advance(1);
+  store_tile(0);
+  load_k_tile(ld_k, ld_tile * kBN);  // staging registers always hold the tile after the one in LDS
+  load_v_tile(ld_v, ld_tile * kBN);
+  cursor_advance(1);
+  // the first step runs the "previous tile" output product with weights of zero, from buffer 2: make
+  // what it multiplies finite
+  auto clear_vt = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < DV * kBN * 2 / 16 / kThreads; ++i)
+      ((u32x4*)&sm.vt[buf][0][0])[i * kThreads + tid] = u32x4{0u, 0u, 0u, 0u};
+  };
+  clear_vt(2);
+
+  while (true) {
+    // ---- one tile of work: 256 query rows of (work.b, work.h) against work.n_tiles K/V tiles --------
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));  // Q has arrived, and sits in accumulation registers
+    reset_state();
+    __syncthreads();
+    const int n_tiles = work.n_tiles;
+    r0 = work.qtile * kBM + wave * 64;
+    int wave_limit = p.S_k;  // tokens this wavefront can see
+    if (p.causal) {
+      int lastw = r0 + 63;
+      lastw = lastw < p.S_q ? lastw : p.S_q - 1;
+      wave_limit = lastw + off + 1;  // (<= 0 for a wavefront whose rows are all past S_q: it only stages)
+    }
+    // tiles wholly visible to every row of this wavefront need no mask; tiles past its last row are
+    // staging only -- the pending block is finished before the first of those overwrites its buffer
+    int n_plain = p.S_k / kBN;
+    if (p.causal) {
+      const int vis = (r0 + off + 1) / kBN;  // tiles entirely at or before the first row's limit
+      n_plain = vis < n_plain ? vis : n_plain;
+    }
+    n_plain = n_plain < n_tiles ? n_plain : n_tiles;
+    int n_compute = wave_limit > 0 ? (wave_limit + kBN - 1) / kBN : 0;
+    n_compute = n_compute < n_tiles ? n_compute : n_tiles;
+    n_plain = n_plain < n_compute ? n_plain : n_compute;
+
+    // The bulk of the steps -- unmasked, three at a time, one per buffer -- run with constant buffer
+    // indices; they stop two tiles short of the end of the tile of work, so that their loads never
+    // leave its K/V head (the stream cursor stands in that head throughout, and is moved past those
+    // steps in one go afterwards).  The steps after (the diagonal, and what the groups of three leave
+    // over) run one more copy of the body, the masked one, which takes the buffer index as a value --
+    // its LDS bases cost a dozen additions per step -- and its loads from the stream cursor.
+    int hot_end = n_plain < n_tiles - 2 ? n_plain : n_tiles - 2;
+    hot_end = hot_end > 0 ? hot_end / 3 * 3 : 0;
+    int it = 0;
+    for (; it < hot_end; it += 3) {
+      tile_step(it, std::false_type{}, std::integral_constant<int, 0>{}, ld_k, ld_v, it * kBN + 2 * kBN);
+      tile_step(it + 1, std::false_type{}, std::integral_constant<int, 1>{}, ld_k, ld_v, it * kBN + 3 * kBN);
+      tile_step(it + 2, std::false_type{}, std::integral_constant<int, 2>{}, ld_k, ld_v, it * kBN + 4 * kBN);
+    }
+    cursor_advance(hot_end);
+    int cur = 0;  // slot % 3: the LDS buffer of the tile the next step computes
+    for (; it < n_compute; ++it, cur = cur == 2 ? 0 : cur + 1) {
+      tile_step(it, std::true_type{}, cur, ld_k, ld_v, ld_tile * kBN);
+      cursor_advance(1);
+    }
+    if (pending) drain(cur == 0 ? 2 : cur - 1);
+    const int n_slots = (n_tiles + 2) / 3 * 3;
+    for (; it < n_slots; ++it, cur = cur == 2 ? 0 : cur + 1) {  // (past this wavefront's last row, or padding)
+      staging_step(cur, ld_k, ld_v, ld_tile * kBN);
+      cursor_advance(1);
+    }
+
+    // ---- on to the next tile of work: its first K/V tile is in LDS already and its second in the
+    //      staging registers; its Q is loaded under the output epilogue of this one ------------------
+    Work next;
+    const int next_seq = next_work(seq, next);
+    __syncthreads();  // every wavefront is through its drain: the buffer of the last tile is free
+    // (Q of this tile of work is dead: its registers take the next one, which arrives under the epilogue)
+    if (next_seq < n_seq) {
+      load_q(next, qf);
+      // the first step of the next tile of work multiplies buffer 2 by weights of zero: whatever this
+      // tile of work left there must not reach it (a zero times an infinity)
+      clear_vt(2);
+    }
+    write_rows(work);
+    if (next_seq >= n_seq) break;
+    work = next;
+    seq = next_seq;
   }
 }
 
 template <int DQK, int DV>
 hipError_t launch64(const PrefillParams& p, hipStream_t s) {
-  const int n_qtiles = (p.S_q + 255) / 256;
-  const int64_t n_wg = (int64_t)n_qtiles * p.n_q * p.B;
-  if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-  const int xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
-  launch_kernel(0, prefill_mfma64_kernel<DQK, DV>, dim3((unsigned)n_wg), dim3(256), 0, s, p, n_qtiles, xcd_aware);
+  Schedule64 sch;
+  sch.n_qtiles = (p.S_q + 255) / 256;
+  sch.n_pairs = (sch.n_qtiles + 1) / 2;
+  const int64_t n_units = (int64_t)sch.n_pairs * p.n_q * p.B;
+  if (n_units > 0x3fffffff) return hipErrorInvalidValue;
+  sch.n_units = (int)n_units;
+  sch.xcd_aware = ((p.B * p.n_k) % kXcds == 0) ? 1 : 0;
+  // one persistent workgroup per compute unit (a workgroup fills one: a wavefront per SIMD with the
+  // whole register file), fewer if there is less work
+  const int n_wg = sch.n_units < p.n_cu ? sch.n_units : p.n_cu;
+  launch_kernel(0, prefill_mfma64_kernel<DQK, DV>, dim3((unsigned)n_wg), dim3(256), 0, s, p, sch);
   return hipGetLastError();
 }
 
