@@ -39,9 +39,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=None,
-                    choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k", "augq_1p5b", "augq_10b"],
-                    help="the last two time the augmented-Q feed-forward of a decode step (16 tokens) at "
-                         "Sigma-1.5B / Sigma-10B widths: weight bytes per second")
+                    choices=["decode_32k", "decode_4k", "paged_ragged", "prefill_8k", "decode_32k_halfk",
+                             "prefill_8k_halfk", "augq_1p5b", "augq_10b"],
+                    help="*_halfk: the same shapes with K heads of half width (d_qk 64, d_v 128); the last two "
+                         "time the augmented-Q feed-forward of a decode step (16 tokens) at Sigma-1.5B / "
+                         "Sigma-10B widths: weight bytes per second")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="default run: headline workload only")
     ap.add_argument("--top-k", type=int, default=-1,
@@ -134,7 +136,8 @@ def run_workload(workload, steps, warmup, topk, want_cpu, torch, binding, inputs
         k_dev, v_dev = host["k"].to(dev), host["v"].to(dev)
         out = torch.empty((cfg["B"], cfg["n_q"], cfg["S"], cfg["d_v"]), dtype=q.dtype, device=dev)
         S = cfg["S"]
-        flops = 4.0 * cfg["d_qk"] * cfg["B"] * cfg["n_q"] * S * (S + 1) / 2  # masked half not counted
+        # two products of d_qk and d_v multiply-adds per visible (query, key) pair; masked half not counted
+        flops = 2.0 * (cfg["d_qk"] + cfg["d_v"]) * cfg["B"] * cfg["n_q"] * S * (S + 1) / 2
 
     def step(i):
         if kind == "decode":
@@ -334,7 +337,7 @@ def cpu_baseline(cfg, host, kind, kv_bytes, topk=-1):
     else:
         rows = np.arange(0, cfg["S"], 128, dtype=np.int32)  # every 128th query row, all heads
         fn = lambda: oracle.prefill(a(host["q"]), a(host["k"]), a(host["v"]), causal=True, rows=rows)
-        work = float(sum(4.0 * cfg["d_qk"] * cfg["B"] * cfg["n_q"] * (int(i) + 1) for i in rows)) / 1e12
+        work = float(sum(2.0 * (cfg["d_qk"] + cfg["d_v"]) * cfg["B"] * cfg["n_q"] * (int(i) + 1) for i in rows)) / 1e12
         unit, sample = "TFLOP/s", "every 128th query row of every head (%d rows), one evaluation" % len(rows)
     # repeat the sample until about ten seconds of CPU work have been timed (at least one evaluation)
     reps, t0 = 0, time.perf_counter()

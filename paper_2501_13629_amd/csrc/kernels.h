@@ -95,7 +95,7 @@ hipError_t launch_prefill_generic(const PrefillParams& p, int dtype, hipStream_t
 bool prefill_mfma_supported(const PrefillParams& p, int dtype);
 // variant: 0 choose; 8 / 4 wavefronts of 32 rows; 2 = the 64-row kernel where supported
 hipError_t launch_prefill_mfma(const PrefillParams& p, int variant, hipStream_t s);
-bool prefill_mfma64_supported(const PrefillParams& p, int dtype);       // d_qk = d_v = 128 only
+bool prefill_mfma64_supported(const PrefillParams& p, int dtype);       // d_v = 128, d_qk = 128 or 64
 hipError_t launch_prefill_mfma64(const PrefillParams& p, hipStream_t s);  // 64 query rows per wavefront
 int topk_max_k();
 bool topk_scores_mfma_supported(const TopkParams& p, int dtype);

@@ -108,7 +108,7 @@ struct Schedule64 {
 
 template <int DQK, int DV>
 __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p, Schedule64 sch) {
-  static_assert(DQK == 128 && DV == 128, "the slot schedule below is laid out for four phases of eight fragments");
+  static_assert((DQK == 128 || DQK == 64) && DV == 128, "head widths this kernel is laid out for");
   constexpr int KS = DQK / 16;  // k-steps of the score product (16 channels each)
   constexpr int CB = DV / 32;   // 32-channel blocks of the output
   constexpr int kThreads = 256;
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   };
 
   // ---- global -> register -> LDS staging of one K/V tile (every thread takes part in both) ----------
-  // K tile = 64 rows x d_qk channels: 16 threads share a row (16 bytes each) and take KLD rows next
+  // K tile = 64 rows x d_qk channels: d_qk / 8 threads share a row (16 bytes each) and take KLD rows next
   // to each other, so one per-lane offset per tile serves all of a thread's loads through the
   // immediate field.  V tile: 16 token quads x d_v/8 channel chunks, one (quad, chunk) per thread: it
   // loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to high:
@@ -215,8 +215,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
   const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
   const int v_voff = (4 * v_tq) * (DV * 2) + v_c8 * 16;
-  static_assert(DQK / 8 == 16 && kThreads / 16 * KLD == kBN, "16 threads per K row");
-  const int k_row = (tid >> 4) * KLD, k_chunk = tid & 15;
+  constexpr int kRowThreads = DQK / 8;  // threads that share a K row
+  static_assert(kThreads / kRowThreads * KLD == kBN, "whole rows per thread");
+  const int k_row = (tid / kRowThreads) * KLD, k_chunk = tid % kRowThreads;
   const int k_voff = k_row * (DQK * 2) + k_chunk * 16;
   u32x4 kst[KLD], vst[4];
   // (t0: first token of the tile inside the head that the resource describes)
@@ -306,6 +307,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   // computed again.  Weights stay below 2^40, inside bf16 / fp32 range with room for the sums; the final
   // division by the row sum removes the reference.
   constexpr float kBig = 1.0995116e12f;  // 2^40
+  // Of the 32 half-pieces of a block's weights, how many run under the output-product phase of their
+  // window (4 CB slots) and how many under the score phase (2 KS slots): in proportion, and even.
+  constexpr int kHalvesA = 2 * ((16 * 4 * CB + (4 * CB + 2 * KS) / 2) / (4 * CB + 2 * KS));
   float l_blk[2][2] = {{0.f, 0.f}, {0.f, 0.f}};  // [token block][row block]: sum of the block's weights
   // two of a row block's 16 weights of a token block
   auto weights_piece = [&](int blk, int qb, int i) {
@@ -437,10 +441,14 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       // the vector ALU's operand ports for a good part of them, so two matrix instructions back to
       // back, or a long run of vector work, both leave one of the pipes idle.  Every matrix
       // instruction is therefore followed by a "slot" with an even share of all the other work of
-      // the step.  Slots are numbered g = 0..63 (phase p covers 16 p .. 16 p + 15):
-      //   the weights of a token block as 32 half-pieces -- even: two exponentials, odd: pack and sum
-      //   -- one per slot: block 0 at g = 16..47 (its scores are complete after phase 1, its output
-      //   product starts with phase 4), block 1 at g = 48..63 and on into g = 0..15 of the next step;
+      // the step.  Slots are numbered g = 0 .. 2 kFrags - 1, two per fragment; phase 1 (scores of block
+      // 0) covers the first 2 KS of them, phase 2 (output product of the previous tile's block 1) the
+      // next 4 CB, phase 3 (scores of block 1) 2 KS, phase 4 (output product of block 0) 4 CB:
+      //   the weights of a token block as 32 half-pieces -- even: two exponentials, odd: pack and sum --
+      //   spread evenly over the slots of two phases (one per slot at d_qk = 128, four per three slots
+      //   at d_qk = 64): block 0 under phases 2-3 (its scores are complete after phase 1, its output
+      //   product starts with phase 4), block 1 under phase 4 and on into phase 1 of the next step
+      //   (an even number of them on each side: a pair of halves never straddles two steps);
       //   row block 0 / 1 alternate in groups of four pieces so that everything is ready when the
       //   output product asks for it; the range check that closes a block follows its last half;
       //   staging (LDS stores of the next tile, then the loads of the one after) on odd slots.
@@ -469,15 +477,31 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         else if constexpr (idx == KLD + 8) load_k_tile(ld_k, ld_tok);
         else load_v_tile(ld_v, ld_tok);
       };
+      // halves [lo, hi) of a block's weights, in order
+      auto halves = [&](auto blkc, auto loc, auto hic) {
+        constexpr int lo = decltype(loc)::value, hi = decltype(hic)::value;
+        static_for<lo, hi>([&](auto hc) { weights_half(blkc, hc, tp); });
+      };
       auto slot = [&](auto gc) {
         constexpr int g = decltype(gc)::value;
-        if constexpr (MASKED && g == 16) mask_block(std::integral_constant<int, 0>{});
-        if constexpr (MASKED && g == 48) mask_block(std::integral_constant<int, 1>{});
-        if constexpr (g >= 16 && g < 48) weights_half(std::integral_constant<int, 0>{}, std::integral_constant<int, g - 16>{}, tp);
-        if constexpr (g >= 48) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, g - 48>{}, tp);
-        if constexpr (g < 16) weights_half(std::integral_constant<int, 1>{}, std::integral_constant<int, 16 + g>{}, tp);
-        if constexpr (g == 15) close_block(std::integral_constant<int, 1>{});  // the previous tile's second block
-        if constexpr (g == 47) close_block(std::integral_constant<int, 0>{});
+        constexpr int P2 = 2 * G0, P3 = 2 * G1, P4 = 2 * G2;  // first slots of phases 2, 3, 4
+        constexpr int nA = 4 * CB, nB = 2 * KS, HA = kHalvesA, HB = 32 - HA;
+        if constexpr (MASKED && g == P2) mask_block(std::integral_constant<int, 0>{});
+        if constexpr (MASKED && g == P4) mask_block(std::integral_constant<int, 1>{});
+        if constexpr (g >= P2 && g < P3)
+          halves(std::integral_constant<int, 0>{}, std::integral_constant<int, HA * (g - P2) / nA>{},
+                 std::integral_constant<int, HA * (g - P2 + 1) / nA>{});
+        if constexpr (g >= P3 && g < P4)
+          halves(std::integral_constant<int, 0>{}, std::integral_constant<int, HA + HB * (g - P3) / nB>{},
+                 std::integral_constant<int, HA + HB * (g - P3 + 1) / nB>{});
+        if constexpr (g >= P4)
+          halves(std::integral_constant<int, 1>{}, std::integral_constant<int, HA * (g - P4) / nA>{},
+                 std::integral_constant<int, HA * (g - P4 + 1) / nA>{});
+        if constexpr (g < P2)
+          halves(std::integral_constant<int, 1>{}, std::integral_constant<int, HA + HB * g / nB>{},
+                 std::integral_constant<int, HA + HB * (g + 1) / nB>{});
+        if constexpr (g == P2 - 1) close_block(std::integral_constant<int, 1>{});  // the previous tile's second block
+        if constexpr (g == P4 - 1) close_block(std::integral_constant<int, 0>{});
         // staging on odd slots: the K stores, then at once the K loads of the tile after (the longer a
         // load has before its store, a step later, the less that store waits), the V stores, the V loads
         if constexpr ((g & 1) && g < 2 * KLD) stage_item(std::integral_constant<int, g / 2>{});
@@ -488,7 +512,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
 
       static_for<0, kFrags>([&](auto fc) {
         constexpr int f = decltype(fc)::value;
-        constexpr int phase = f / 8 + 1, j = f % 8;  // step inside the phase
+        constexpr int phase = f < G0 ? 1 : f < G1 ? 2 : f < G2 ? 3 : 4;
+        constexpr int j = f - (phase == 1 ? 0 : phase == 2 ? G0 : phase == 3 ? G1 : G2);  // step inside the phase
         const u32x4 a = fr[f % kRing];
         auto matrix = [&](auto qc) {
           constexpr int qb = decltype(qc)::value;
@@ -520,10 +545,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     uint32_t vt_last[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) vt_last[c] = vt_lane[c] + (uint32_t)vprev * kVBuf;
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-      for (int i = 4; i < 8; ++i) weights_piece(1, qb, i);  // the halves the next step would have taken
+    // the halves the next step would have taken: kHalvesA .. 31, whole pieces
+    static_for<kHalvesA / 2, 16>([&](auto pc) {
+      constexpr int h = 2 * decltype(pc)::value, group = h / 8;
+      weights_piece(1, group & 1, (group >> 1) * 4 + (h % 8) / 2);
+    });
     close_block(std::integral_constant<int, 1>{});
     static_for<0, 2 * CB>([&](auto jc) {
       constexpr int j = decltype(jc)::value, sh = (j / CB) * 4;
@@ -722,12 +748,13 @@ hipError_t launch64(const PrefillParams& p, hipStream_t s) {
 
 bool prefill_mfma64_supported(const PrefillParams& p, int dtype) {
   // (the staging loads run up to two tiles past the end of a head: keep them inside the 32-bit offset)
-  return dtype == 1 && p.d_qk == 128 && p.d_v == 128 && (int64_t)(p.S_k + 2 * kBN) * 128 * 2 < (1ll << 31);
+  return dtype == 1 && (p.d_qk == 128 || p.d_qk == 64) && p.d_v == 128 &&
+         (int64_t)(p.S_k + 2 * kBN) * 128 * 2 < (1ll << 31);
 }
 
 hipError_t launch_prefill_mfma64(const PrefillParams& p, hipStream_t s) {
   if (p.B == 0) return hipSuccess;
-  return launch64<128, 128>(p, s);
+  return p.d_qk == 128 ? launch64<128, 128>(p, s) : launch64<64, 128>(p, s);
 }
 
 }  // namespace diffqkv

@@ -32,6 +32,10 @@ CONFIGS = {
     "prefill_8k": dict(index=4, kind="prefill", dtype="bf16", B=2, n_q=32, n_k=4, n_v=16, d_qk=128, d_v=128,
                        S=8192),
 }
+# The same long-context decode and prefill shapes with the K heads at half width (the paper's second
+# compression axis, section 2, observation 2: d_qk = d_v / 2); bench workloads beside the five above.
+CONFIGS["decode_32k_halfk"] = dict(CONFIGS["decode_32k"], index=5, d_qk=64)
+CONFIGS["prefill_8k_halfk"] = dict(CONFIGS["prefill_8k"], index=6, d_qk=64)
 
 _CHUNK = 1 << 22
 

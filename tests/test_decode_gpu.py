@@ -142,6 +142,11 @@ def test_config3_decode_32k_full():
     run_case(inputs.config("decode_32k"))
 
 
+def test_half_k_decode_32k_full():
+    """The 32k decode workload with K heads of half width (d_qk 64, d_v 128), default launch configuration."""
+    run_case(inputs.config("decode_32k_halfk"))
+
+
 def test_bytes_model_sanity_k_heads():
     """Fewer K heads must never make the answer depend on anything but the head map: the same
     K/V data seen through n_k = 16 (K duplicated per V head, the 'group sharing' workaround of the

@@ -51,41 +51,66 @@ def test_prefix_plus_chunk_and_noncausal(dtype):
     run(cfg, causal=False)
 
 
+@pytest.mark.parametrize("d_qk", [128, 64])
 @pytest.mark.parametrize("variant", [2, 4, 8])
-def test_every_mfma_variant(variant):
-    """The three matrix-core kernels (64 rows per wavefront; 4 or 8 wavefronts of 32 rows) on lengths that
-    end inside a tile, a wavefront's rows and a workgroup's rows, with and without a cached prefix."""
+def test_every_mfma_variant(variant, d_qk):
+    """The three matrix-core kernels (64 rows per wavefront; 4 or 8 wavefronts of 32 rows), at full and at
+    half K width, on lengths that end inside a tile, a wavefront's rows and a workgroup's rows, with and
+    without a cached prefix; several query tiles per head, so that a workgroup of the 64-row kernel
+    walks through more than one tile of work."""
     for S in (1, 63, 64, 65, 255, 256, 257, 700, 1100):
-        run(inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, S=S, index=73 + S % 7), variant=variant)
-    cfg = inputs.config("prefill_8k", B=2, n_q=4, n_k=2, n_v=2, S=300, S_k=1000, index=74)
+        run(inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, d_qk=d_qk, S=S, index=73 + S % 7), variant=variant)
+    cfg = inputs.config("prefill_8k", B=2, n_q=4, n_k=2, n_v=2, d_qk=d_qk, S=300, S_k=1000, index=74)
     run(cfg, causal=True, variant=variant)
     run(cfg, causal=False, variant=variant)
-    run(inputs.config("prefill_8k", B=1, n_q=2, n_k=1, n_v=1, S=130, S_k=131, index=75), variant=variant)
+    run(inputs.config("prefill_8k", B=1, n_q=2, n_k=1, n_v=1, d_qk=d_qk, S=130, S_k=131, index=75), variant=variant)
 
 
-@pytest.mark.parametrize("variant", [0, 8])
-def test_wide_score_range_moves_the_softmax_reference(variant):
-    """Unit softmax scale on N(0,1) data of width 128 (scores of standard deviation ~11, spread over more
-    than a hundred log2 units), and rows whose largest score arrives late: the reference of the online
-    softmax has to rise several times on the way, also in the middle of a sequence."""
-    cfg = inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, S=900, index=76)
+def test_more_work_than_workgroups():
+    """More pairs of query tiles than compute units: the persistent workgroups of the 64-row kernel take
+    several pairs each, of unequal length (a cached prefix, a ragged last tile), through one K/V stream."""
+    run(inputs.config("prefill_8k", B=3, n_q=16, n_k=2, n_v=4, S=2900, S_k=3001, index=78))
+    run(inputs.config("prefill_8k", B=3, n_q=16, n_k=2, n_v=4, d_qk=64, S=2900, index=79), causal=False)
+
+
+WIDE = {
+    # one token that dominates every later row, and one that nearly vanishes
+    "late_spike": lambda d: (d["k"][:, :, 517].mul_(6.0), d["k"][:, :, 100].mul_(-6.0)),
+    # the dominant token sits in the very first block: the reference is set high at once and everything
+    # after it is tiny against it
+    "first_block_dominates": lambda d: (d["k"][:, :, 3].mul_(8.0),),
+    # scores that keep rising along the sequence: the reference has to follow, block after block
+    "rising": lambda d: (d["k"].mul_(torch.linspace(0.2, 3.0, d["k"].shape[2]).view(1, 1, -1, 1).to(d["k"].dtype)),),
+}
+
+
+@pytest.mark.parametrize("case", sorted(WIDE))
+@pytest.mark.parametrize("variant,d_qk", [(0, 128), (0, 64), (8, 128)])
+def test_wide_score_range_moves_the_softmax_reference(variant, d_qk, case):
+    """Unit softmax scale on N(0,1) data (scores of standard deviation ~8-11, spread over more than a
+    hundred log2 units), shaped so that the reference of the online softmax has to rise on the way: late
+    in the sequence, never after the first block, or steadily."""
+    cfg = inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, d_qk=d_qk, S=900, index=76)
     d = inputs.make_prefill(cfg)
-    d["k"][:, :, 517] *= 6.0   # one token that dominates every later row ...
-    d["k"][:, :, 100] *= -6.0  # ... and one that nearly vanishes
+    WIDE[case](d)
+    # (rows that attend to a single token return that token's V row: halve V, exactly, so that the bf16
+    #  rounding of an output near max |V| -- half an ulp of 2^-5 above 4 -- stays well inside the tolerance)
+    d["v"].mul_(0.5)
     binding.diffqkv_set_tuning(prefill_waves=variant)
     out, lse = binding.diffqkv_prefill(util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"]), scale=1.0, want_lse=True)
     ref, ref_lse = oracle.prefill(inputs.as_numpy(d["q"]), inputs.as_numpy(d["k"]), inputs.as_numpy(d["v"]), scale=1.0)
-    util.check(out, ref, "bf16", "variant %d" % variant)
+    util.check(out, ref, "bf16", "variant %d, %s" % (variant, case))
     util.check_lse(lse, ref_lse)
 
 
+@pytest.mark.parametrize("d_qk", [128, 64])
 @pytest.mark.parametrize("variant", [0, 4, 8])
-def test_memory_behind_the_tensors_is_never_used(variant):
+def test_memory_behind_the_tensors_is_never_used(variant, d_qk):
     """K and V sit at the front of larger allocations whose remainder is NaN, and the lengths end inside a
     tile: whatever the staging loads fetch past the last row of the last head -- in this tile or in the
     tiles a kernel loads ahead -- must not reach the output (NaN times a zero weight is still NaN)."""
     for S, S_k in ((37, 37), (300, 300), (130, 451)):
-        cfg = inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, S=S, S_k=S_k, index=77)
+        cfg = inputs.config("prefill_8k", B=1, n_q=4, n_k=1, n_v=2, d_qk=d_qk, S=S, S_k=S_k, index=77)
         d = inputs.make_prefill(cfg)
         dev = {}
         for name in ("k", "v"):
@@ -119,3 +144,8 @@ def test_config5_prefill_8k_full():
     query row of every head of both sequences is compared with the oracle, element by element."""
     cfg = inputs.config("prefill_8k")
     run(cfg)
+
+
+def test_half_k_prefill_8k_full():
+    """The 8k prefill workload with K heads of half width, every row of every head against the oracle."""
+    run(inputs.config("prefill_8k_halfk"))
