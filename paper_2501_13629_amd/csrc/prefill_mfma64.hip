@@ -91,7 +91,11 @@ template <int DQK, int DV>
 struct Smem64 {
   static constexpr int kKPitch = DQK + 8;  // bf16 elements per K row (16 B of padding)
   uint16_t k[3][kBN][kKPitch];
-  uint16_t vt[3][DV][kBN];
+  // V tiles as they are in memory, token-major; the transposition that the output product's A operand
+  // needs happens in the LDS read (ds_read_b64_tr_b16).  64 bytes of padding per row: the four rows a
+  // half-wavefront reads in one such instruction then fall on four disjoint quarters of the banks.
+  static constexpr int kVPitch = DV + 32;  // bf16 elements per V row
+  uint16_t v[3][kBN][kVPitch];
   // one slice per wavefront through which a block of 32 output rows leaves (see the epilogue)
   static constexpr int kOutPitch = DV * 2 + 8;  // bytes per row; the 8 spread the rows over the banks
   char out[4][32 * kOutPitch];
@@ -203,23 +207,18 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   // ---- global -> register -> LDS staging of one K/V tile (every thread takes part in both) ----------
   // K tile = 64 rows x d_qk channels: d_qk / 8 threads share a row (16 bytes each) and take KLD rows next
   // to each other, so one per-lane offset per tile serves all of a thread's loads through the
-  // immediate field.  V tile: 16 token quads x d_v/8 channel chunks, one (quad, chunk) per thread: it
-  // loads 4 tokens x 8 channels and transposes them in registers.  V thread bits, low to high:
-  // chunk[2:0], quad-order bit 1, chunk[3] (d_v = 128 only), quad-order bit 0, 16-token group -- lanes
-  // that write the same channel rows in one instruction differ in the half-granule they write.
+  // immediate field.  The V tile (64 rows x d_v channels) is staged the same way, VLD rows per thread.
   constexpr int KLD = kBN * (DQK / 8) / kThreads;
-  constexpr int kChunkBits = (DV == 128) ? 4 : 3;
-  constexpr int kVItems = 16 * (DV / 8);
-  const bool v_role = kVItems >= kThreads || wave < kVItems / 64;  // whole wavefronts; all of them at d_v = 128
-  const int v_c8 = (tid & 7) | ((kChunkBits == 4) ? ((tid >> 1) & 8) : 0);
-  const int v_rest = tid >> (kChunkBits + 1);  // quad-order bit 0, then the 16-token group
-  const int v_tq = ((v_rest >> 1) & 3) * 4 + ((v_rest & 1) | (((tid >> 3) & 1) << 1));
-  const int v_voff = (4 * v_tq) * (DV * 2) + v_c8 * 16;
   constexpr int kRowThreads = DQK / 8;  // threads that share a K row
   static_assert(kThreads / kRowThreads * KLD == kBN, "whole rows per thread");
   const int k_row = (tid / kRowThreads) * KLD, k_chunk = tid % kRowThreads;
   const int k_voff = k_row * (DQK * 2) + k_chunk * 16;
-  u32x4 kst[KLD], vst[4];
+  constexpr int VLD = kBN * (DV / 8) / kThreads;
+  constexpr int kVRowThreads = DV / 8;
+  static_assert(kThreads / kVRowThreads * VLD == kBN, "whole rows per thread");
+  const int v_row = (tid / kVRowThreads) * VLD, v_chunk = tid % kVRowThreads;
+  const int v_voff = v_row * (DV * 2) + v_chunk * 16;
+  u32x4 kst[KLD], vst[VLD];
   // (t0: first token of the tile inside the head that the resource describes)
   auto load_k_tile = [&](rsrc_t k_rsrc, int t0) {
 #pragma unroll
@@ -227,45 +226,33 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, k_voff + t0 * (DQK * 2) + i * (DQK * 2), 0, 0);
   };
   auto load_v_tile = [&](rsrc_t v_rsrc, int t0) {
-    if (v_role) {
 #pragma unroll
-      for (int x = 0; x < 4; ++x)
-        vst[x] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + x * (DV * 2) + t0 * (DV * 2), 0, 0);
-    }
+    for (int i = 0; i < VLD; ++i)
+      vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, v_voff + t0 * (DV * 2) + i * (DV * 2), 0, 0);
   };
   // (LDS addresses as integers: a per-lane part that the step computes once from the buffer index --
   //  folded into the immediates where that index is a constant -- plus an immediate)
   constexpr uint32_t kKBuf = kBN * Smem64<DQK, DV>::kKPitch * 2;  // bytes of one K buffer
-  constexpr uint32_t kVBuf = DV * kBN * 2;                         // bytes of one V^T buffer
+  constexpr uint32_t kVRow = Smem64<DQK, DV>::kVPitch * 2;
+  constexpr uint32_t kVBuf = kBN * kVRow;                          // bytes of one V buffer
   constexpr uint32_t kKRow = Smem64<DQK, DV>::kKPitch * 2;
   const uint32_t k_base = (uint32_t)(uintptr_t)&sm.k[0][0][0];
   const uint32_t k_st = k_base + (uint32_t)(k_row * kKRow + k_chunk * 16);
   auto store_k_item = [&](int i, uint32_t k_st_buf) {  // i in [0, KLD); k_st_buf = k_st + buffer * kKBuf
     *(lds_u32x4*)(k_st_buf + (uint32_t)(i * kKRow)) = kst[i];
   };
-  // The V^T store of channel e of this thread's chunk goes to row 8 v_c8 + e, granule (pos >> 3) ^
-  // swizzle(row) = (pos >> 3) ^ (v_c8 & 7) ^ e: a per-lane byte offset with e XORed into bits 4-6
-  // (they hold nothing else: the row pitch is 128 bytes and pos & 7 < 8 elements = 16 bytes).
-  const int v_pos = vt_pos(4 * v_tq);
-  // (LDS addresses as integers, with the start of the V^T buffers folded into the per-lane part: the
-  //  immediate field of an LDS instruction reaches 64 KiB from there, which covers all three buffers)
-  const uint32_t vt_base = (uint32_t)(uintptr_t)&sm.vt[0][0][0];
-  const uint32_t v_st = vt_base + (uint32_t)(v_c8 * 8 * (kBN * 2) + ((((v_pos >> 3) ^ v_c8) & 7) << 4) + (v_pos & 7) * 2);
-  auto store_v_item = [&](int e, uint32_t v_st_buf) {  // channel e in [0, 8) of this thread's chunk; v_st_buf = v_st + buffer * kVBuf
-    if (v_role) {
-      // word e/2, low or high half, from the 4 tokens
-      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-      u32x2 w;
-      w[0] = __builtin_amdgcn_perm(vst[1][e >> 1], vst[0][e >> 1], sel);
-      w[1] = __builtin_amdgcn_perm(vst[3][e >> 1], vst[2][e >> 1], sel);
-      *(lds_u32x2*)((v_st_buf ^ (uint32_t)(e << 4)) + (uint32_t)(e * (kBN * 2))) = w;
-    }
+  // (with the start of the V buffers folded into the per-lane part: the immediate field of an LDS
+  //  instruction reaches 64 KiB from there, which covers all three buffers)
+  const uint32_t v_base = (uint32_t)(uintptr_t)&sm.v[0][0][0];
+  const uint32_t v_st = v_base + (uint32_t)(v_row * kVRow + v_chunk * 16);
+  auto store_v_item = [&](int i, uint32_t v_st_buf) {  // i in [0, VLD); v_st_buf = v_st + buffer * kVBuf
+    *(lds_u32x4*)(v_st_buf + (uint32_t)(i * kVRow)) = vst[i];
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < KLD; ++i) store_k_item(i, k_st + (uint32_t)buf * kKBuf);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) store_v_item(e, v_st + (uint32_t)buf * kVBuf);
+    for (int i = 0; i < VLD; ++i) store_v_item(i, v_st + (uint32_t)buf * kVBuf);
   };
 
   // ---- state of the tile of work in hand ----------------------------------------------------------------
@@ -371,18 +358,23 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
       l_blk[blk][qb] = 0.f;
     }
   };
-  // V^T fragment of 16-token step kq, channel block cb, from tile buffer vb: row 32 cb + n, granule
-  // (2 kq + half) ^ swizzle(row).  The swizzle of row 32 cb + n is that of row n with bit 2 flipped for
-  // odd cb, and 2 kq only sets bits 1-2, so the granule is (swizzle(n) ^ half) ^ C with C = 2 kq ^
-  // 4 (cb & 1), one of 0, 2, 4, 6: four per-lane byte offsets serve every fragment, the rest of the
-  // address is an immediate.
-  uint32_t vt_lane[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) vt_lane[c] = vt_base + (uint32_t)(n * (kBN * 2) + (((vt_swizzle(n) ^ half) ^ (2 * c)) << 4));
-  auto vt_frag = [&](const uint32_t (&vt_buf)[4], auto kqc, auto cbc) {  // vt_buf[c] = vt_lane[c] + buffer * kVBuf
+  // V^T fragment of 16-token step kq (0..3 within the tile), channel block cb: lane (half, n) needs
+  // channel 32 cb + n of the eight tokens 16 kq + 4 half + {0..3} and + 8 (the token order the score
+  // layout produces).  A transposing LDS read hands each lane of a 16-lane group four values: element
+  // e of lane l comes from the 8 bytes that lane (l / 4 + 4 e) of the group addressed, taking its
+  // element l % 4.  So lane L of a group addresses token row (L / 4), channels 4 (L % 4) .. + 3 of the
+  // group's 16 channels, and receives channel L of four consecutive tokens; two reads make a fragment.
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const int tr_group = lane >> 4, tr_l = lane & 15;
+  const uint32_t v_lane = v_base + (uint32_t)((4 * (tr_group >> 1) + (tr_l >> 2)) * kVRow + (16 * (tr_group & 1) + 4 * (tr_l & 3)) * 2);
+  auto vt_frag = [&](uint32_t v_buf, auto kqc, auto cbc) {  // v_buf = v_lane + buffer * kVBuf
     constexpr int kq = decltype(kqc)::value, cb = decltype(cbc)::value;
-    constexpr int c = ((2 * kq) ^ (4 * (cb & 1))) / 2;
-    return *(const lds_u32x4*)(vt_buf[c] + (uint32_t)(32 * cb * (kBN * 2)));
+    const uint32_t at = v_buf + (uint32_t)(16 * kq * kVRow + 32 * cb * 2);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)at);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(at + 8 * kVRow));
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    return u32x4{l2[0], l2[1], h2[0], h2[1]};
   };
   const uint32_t k_lane = k_base + (uint32_t)(n * kKRow + 16 * half);  // this lane's K fragment of row block 0, k-step 0
 
@@ -407,12 +399,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
     // the step's LDS bases (constants folded into the immediates in the copies with a constant index)
     const uint32_t k_cur = k_lane + (uint32_t)cur * kKBuf;
     const uint32_t k_st_next = k_st + (uint32_t)next * kKBuf, v_st_next = v_st + (uint32_t)next * kVBuf;
-    uint32_t vt_cur[4], vt_prev[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      vt_cur[c] = vt_lane[c] + (uint32_t)cur * kVBuf;
-      vt_prev[c] = vt_lane[c] + (uint32_t)prev * kVBuf;
-    }
+    const uint32_t vt_cur = v_lane + (uint32_t)cur * kVBuf, vt_prev = v_lane + (uint32_t)prev * kVBuf;
     {
       // fragment order: K block 0 | V^T of the previous tile's block 1 | K block 1 | V^T block 0
       constexpr int G0 = KS, G1 = KS + 2 * CB, G2 = 2 * KS + 2 * CB, kFrags = 2 * KS + 4 * CB;
@@ -473,8 +460,8 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         // (unconditional: past the last tile of the last piece of work the stores park stale registers
         //  in a buffer nobody reads, and the loads go to an empty buffer resource and return zeros)
         if constexpr (idx < KLD) store_k_item(idx, k_st_next);
-        else if constexpr (idx < KLD + 8) store_v_item(idx - KLD, v_st_next);
-        else if constexpr (idx == KLD + 8) load_k_tile(ld_k, ld_tok);
+        else if constexpr (idx < KLD + VLD) store_v_item(idx - KLD, v_st_next);
+        else if constexpr (idx == KLD + VLD) load_k_tile(ld_k, ld_tok);
         else load_v_tile(ld_v, ld_tok);
       };
       // halves [lo, hi) of a block's weights, in order
@@ -505,9 +492,9 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         // staging on odd slots: the K stores, then at once the K loads of the tile after (the longer a
         // load has before its store, a step later, the less that store waits), the V stores, the V loads
         if constexpr ((g & 1) && g < 2 * KLD) stage_item(std::integral_constant<int, g / 2>{});
-        if constexpr (g == 2 * KLD + 1) stage_item(std::integral_constant<int, KLD + 8>{});
-        if constexpr ((g & 1) && g >= 2 * KLD + 3 && g < 2 * KLD + 3 + 16) stage_item(std::integral_constant<int, KLD + (g - 2 * KLD - 3) / 2>{});
-        if constexpr (g == 2 * KLD + 3 + 16) stage_item(std::integral_constant<int, KLD + 9>{});
+        if constexpr (g == 2 * KLD + 1) stage_item(std::integral_constant<int, KLD + VLD>{});
+        if constexpr ((g & 1) && g >= 2 * KLD + 3 && g < 2 * KLD + 3 + 2 * VLD) stage_item(std::integral_constant<int, KLD + (g - 2 * KLD - 3) / 2>{});
+        if constexpr (g == 2 * KLD + 3 + 2 * VLD) stage_item(std::integral_constant<int, KLD + VLD + 1>{});
       };
 
       static_for<0, kFrags>([&](auto fc) {
@@ -542,9 +529,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   };
   // The block that is still in flight after the last step a wavefront computes.
   auto drain = [&](int vprev) {  // vprev: buffer of the last tile computed
-    uint32_t vt_last[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) vt_last[c] = vt_lane[c] + (uint32_t)vprev * kVBuf;
+    const uint32_t vt_last = v_lane + (uint32_t)vprev * kVBuf;
     // the halves the next step would have taken: kHalvesA .. 31, whole pieces
     static_for<kHalvesA / 2, 16>([&](auto pc) {
       constexpr int h = 2 * decltype(pc)::value, group = h / 8;
@@ -648,9 +633,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   // the first step runs the "previous tile" output product with weights of zero, from buffer 2: make
   // what it multiplies finite
   auto clear_vt = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < DV * kBN * 2 / 16 / kThreads; ++i)
-      ((u32x4*)&sm.vt[buf][0][0])[i * kThreads + tid] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = tid; i < (int)(kVBuf / 16); i += kThreads) ((u32x4*)&sm.v[buf][0][0])[i] = u32x4{0u, 0u, 0u, 0u};
   };
   clear_vt(2);
 

@@ -347,6 +347,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(TopkParams p) 
   }
 
   // ---- pass 2: sum of exponentials; candidates into LDS (any order) --------------------------------------
+  // (positions past the previous ones were loaded as -inf: their exponential is zero; candidates are a
+  //  few hundred of tens of thousands, so one vote per four positions decides whether to look closer)
   float l = 0.f;
   for (int t0 = 0; t0 < ntiles; t0 += kRegTiles) {
     if (!resident) load_tiles(t0);
@@ -357,13 +359,12 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(TopkParams p) 
       uint32_t key[4];
 #pragma unroll
       for (int x = 0; x < 4; ++x) {
-        const bool live = j + x < prev;
-        if (live) l += exp2f(v[u][x] - m);
+        l += __builtin_amdgcn_exp2f(v[u][x] - m);  // (arguments <= 0; results below the normal range count as zero)
         key[x] = order_key(v[u][x]);
-        c[x] = fast && live && (all || (search && (key[x] >> (32 - kCoarseBits)) >= coarse));
+        c[x] = fast && j + x < prev && (all || (search && (key[x] >> (32 - kCoarseBits)) >= coarse));
       }
+      if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;
       const uint64_t b0 = __ballot(c[0]), b1 = __ballot(c[1]), b2 = __ballot(c[2]), b3 = __ballot(c[3]);
-      if ((b0 | b1 | b2 | b3) == 0) continue;
       int base = 0;
       if (lane == 0) base = atomicAdd(&n_cand_sh, __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
       base = __shfl(base, 0, 64);
@@ -377,7 +378,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(TopkParams p) 
         }
     }
   }
-  if (tid == 0) l += exp2f(s[Tb - 1] - m);
+  if (tid == 0) l += __builtin_amdgcn_exp2f(s[Tb - 1] - m);
   l = block_sum(l, red);  // (its barriers also publish the candidates)
   const float inv_l = 1.f / l;
 
