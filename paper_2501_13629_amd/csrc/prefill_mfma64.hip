@@ -447,10 +447,23 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
         settle_v(s[0][blk], s[1][blk]);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-          // register r is allowed iff 8 (r/4) + r%4 <= lim: one compare against a constant per register
+          // register r is allowed iff 8 (r/4) + r%4 <= lim: one compare against a constant per register.
+          // Whole blocks are decided first, from wavefront-uniform bounds on lim (rows n = 0..31, halves
+          // 0..1): a block every lane sees in full is left alone -- the unmasked steps that run in this
+          // body take that way out four times -- and one that no lane sees is overwritten without compares.
+          const int tok0 = t0 + 32 * blk;                              // first token of the block
+          const int row_last = p.causal ? r0 + 32 * qb + off : p.S_k;  // last token row n = 0 may see
+          const int lim_lo = (row_last < p.S_k - 1 ? row_last : p.S_k - 1) - tok0 - 4;  // n = 0, half = 1
+          const int lim_hi = (row_last + 31 < p.S_k - 1 ? row_last + 31 : p.S_k - 1) - tok0;  // n = 31, half = 0
+          if (lim_lo >= 27) continue;  // every register of every lane is allowed
+          if (lim_hi < 0) {            // none is
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[qb][blk][r] = -INFINITY;
+            continue;
+          }
           int last = p.causal ? r0 + 32 * qb + n + off : p.S_k - 1;  // last token this row may see
           last = last < p.S_k - 1 ? last : p.S_k - 1;
-          const int lim = last - (t0 + 32 * blk + 4 * half);
+          const int lim = last - (tok0 + 4 * half);
 #pragma unroll
           for (int r = 0; r < 16; ++r) s[qb][blk][r] = (8 * (r >> 2) + (r & 3) <= lim) ? s[qb][blk][r] : -INFINITY;
         }
