@@ -347,8 +347,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(TopkParams p) 
   }
 
   // ---- pass 2: sum of exponentials; candidates into LDS (any order) --------------------------------------
-  // (positions past the previous ones were loaded as -inf: their exponential is zero; candidates are a
-  //  few hundred of tens of thousands, so one vote per four positions decides whether to look closer)
+  // (candidates are a few hundred of tens of thousands: one vote per quad decides whether to look closer)
   float l = 0.f;
   for (int t0 = 0; t0 < ntiles; t0 += kRegTiles) {
     if (!resident) load_tiles(t0);
@@ -359,9 +358,11 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(TopkParams p) 
       uint32_t key[4];
 #pragma unroll
       for (int x = 0; x < 4; ++x) {
-        l += __builtin_amdgcn_exp2f(v[u][x] - m);  // (arguments <= 0; results below the normal range count as zero)
+        const bool live = j + x < prev;  // (a loaded quad may reach into the current token and the padding)
+        const float e = __builtin_amdgcn_exp2f(v[u][x] - m);  // (arguments <= 0; results below the normal range count as zero)
+        l += live ? e : 0.f;
         key[x] = order_key(v[u][x]);
-        c[x] = fast && j + x < prev && (all || (search && (key[x] >> (32 - kCoarseBits)) >= coarse));
+        c[x] = fast && live && (all || (search && (key[x] >> (32 - kCoarseBits)) >= coarse));
       }
       if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;
       const uint64_t b0 = __ballot(c[0]), b1 = __ballot(c[1]), b2 = __ballot(c[2]), b3 = __ballot(c[3]);
