@@ -286,6 +286,10 @@ def bench_augq(args, torch, binding, inputs, dev):
     binding.diffqkv_kernel_timer(False)
     avg = k0 + k1
     value = wbytes / (us * 1e-6) / 1e9
+    traffic, traffic_file = None, os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            traffic = json.load(f).get(args.workload)
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -306,7 +310,9 @@ def bench_augq(args, torch, binding, inputs, dev):
         "config": {"workload": args.workload, "M": M, "hidden": hidden, "inter": inter, "weight_bytes_per_step": wbytes,
                    "weight_sets_in_rotation": n_sets},
         "roofline": {"bound": "hbm", "achieved": round(wbytes / (avg * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(wbytes / (avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(wbytes / (avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_source": None if traffic is None else "stored: profiles/hbm_traffic.json, rocprofv3 --pmc "
+                     "FETCH_SIZE and WRITE_SIZE of an earlier run of this workload, not measured in this run",
                      "kernel": "augq_mfma_kernel<true> + <false> (both launches)", "kernel_avg_us": round(avg, 2),
                      "first_product_us": round(k0, 2), "second_product_us": round(k1, 2),
                      "algorithmic_bytes_per_launch": wbytes},

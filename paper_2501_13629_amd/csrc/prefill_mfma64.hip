@@ -567,13 +567,17 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   auto write_rows = [&](const Work& w) {
     settle_a<CB>(acc);
     constexpr int kOutPitch = Smem64<DQK, DV>::kOutPitch;
-    char* const slice = &sm.out[wave][0];
+    const uint32_t slice = (uint32_t)(uintptr_t)&sm.out[wave][0];
     const int o_row = lane >> 4, o_chunk = lane & 15;
+    // Rows at or past S_q are dropped by the range check of the buffer stores (no branches in here).
+    const int64_t head = (int64_t)w.b * p.n_q + w.h;
+    const rsrc_t o_rsrc = make_rsrc(uniform((const uint16_t*)p.out + head * p.S_q * DV), p.S_q * DV * 2);
+    const rsrc_t lse_rsrc = make_rsrc(uniform((const uint16_t*)(p.lse_out ? p.lse_out + head * p.S_q : nullptr)),
+                                      p.lse_out ? p.S_q * 4 : 0);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      const int my_row = r0 + 32 * qb + n;
       const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);  // both halves hold the full row sum now
-      const float inv = 1.f / l;
+      const float inv = __builtin_amdgcn_rcpf(l);
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -581,17 +585,17 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
           u32x2 x;
           x[0] = pack_bf16x2(acc[qb][cb][4 * q4] * inv, acc[qb][cb][4 * q4 + 1] * inv);
           x[1] = pack_bf16x2(acc[qb][cb][4 * q4 + 2] * inv, acc[qb][cb][4 * q4 + 3] * inv);
-          *(u32x2*)(slice + n * kOutPitch + (32 * cb + 8 * q4 + 4 * half) * 2) = x;
+          *(lds_u32x2*)(slice + (uint32_t)(n * kOutPitch + (32 * cb + 8 * q4 + 4 * half) * 2)) = x;
         }
-      if (my_row < p.S_q && half == 0 && p.lse_out)
-        p.lse_out[((int64_t)w.b * p.n_q + w.h) * p.S_q + my_row] = (m_run[qb] + log2f(l)) * kLn2;
-      uint16_t* const oblock = (uint16_t*)p.out + (((int64_t)w.b * p.n_q + w.h) * p.S_q + r0 + 32 * qb) * DV;
+      // (the two halves of a row store the same value to the same place)
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, (m_run[qb] + __builtin_amdgcn_logf(l)) * kLn2),
+                                            lse_rsrc, (r0 + 32 * qb + n) * 4, 0, 0);
+      u32x4 piece[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int row = 4 * i + o_row;
-        const u32x4 piece = *(const u32x4*)(slice + row * kOutPitch + o_chunk * 16);
-        if (r0 + 32 * qb + row < p.S_q) *(u32x4*)(oblock + row * DV + o_chunk * 8) = piece;
-      }
+      for (int i = 0; i < 8; ++i) piece[i] = *(const lds_u32x4*)(slice + (uint32_t)((4 * i + o_row) * kOutPitch + o_chunk * 16));
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_raw_buffer_store_b128(piece[i], o_rsrc, (r0 + 32 * qb + 4 * i + o_row) * (DV * 2) + o_chunk * 16, 0, 0);
     }
   };
 
@@ -646,7 +650,10 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma64_kernel(PrefillParams p,
   // the first step runs the "previous tile" output product with weights of zero, from buffer 2: make
   // what it multiplies finite
   auto clear_vt = [&](int buf) {
-    for (int i = tid; i < (int)(kVBuf / 16); i += kThreads) ((u32x4*)&sm.v[buf][0][0])[i] = u32x4{0u, 0u, 0u, 0u};
+    static_assert(kVBuf % (16 * kThreads) == 0, "whole rounds of 16-byte stores");
+#pragma unroll
+    for (int i = 0; i < (int)(kVBuf / (16 * kThreads)); ++i)
+      *(lds_u32x4*)(v_base + (uint32_t)buf * kVBuf + (uint32_t)((i * kThreads + tid) * 16)) = u32x4{0u, 0u, 0u, 0u};
   };
   clear_vt(2);
 
