@@ -242,9 +242,10 @@ int diffqkv_append_paged(const diffqkv_shape* shape /* host */, const void* k_ne
  *   q_in [M, hidden], w_gate and w_up [inter, hidden], w_down [hidden, inter] (the layout of a linear
  *   layer: [out features][in features]), q_out [M, hidden] (may not alias q_in).
  * hidden and inter must be multiples of 8.  M is the number of tokens of the step (the batch size in
- * decode); the matrix-core path (bf16, widths that are multiples of 2048 or 3072) is laid out for M <= 16 per
+ * decode); the matrix-core path (bf16, widths of 2048, 3072, 4096 or 6144) is laid out for M <= 16 per
  * pass and repeats the pass for more.  Accumulation is fp32; the intermediate activations are rounded
- * once to `dtype` into the workspace (diffqkv_augment_q_workspace_bytes: M x inter elements).
+ * once to `dtype` into the workspace (diffqkv_augment_q_workspace_bytes: M, rounded up to a multiple of 16,
+ * x inter elements; the layout inside is the library's own).
  * Returns a diffqkv_status; on error nothing is enqueued.
  */
 typedef struct diffqkv_augq_shape {

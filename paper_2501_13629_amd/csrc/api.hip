@@ -607,7 +607,8 @@ static int check_augq(const diffqkv_augq_shape* s) {
 size_t diffqkv_augment_q_workspace_bytes(const diffqkv_augq_shape* shape) {
   if (check_augq(shape) != DIFFQKV_OK) return 0;
   const size_t elem = shape->dtype == DIFFQKV_F32 ? 4 : 2;
-  return ((size_t)shape->M * shape->inter * elem + 255) / 256 * 256;
+  // (whole blocks of 16 tokens: the matrix-core kernels keep the intermediate activations block by block)
+  return ((size_t)((shape->M + 15) / 16 * 16) * shape->inter * elem + 255) / 256 * 256;
 }
 
 int diffqkv_augment_q(const diffqkv_augq_shape* shape, const void* q_in, const void* w_gate, const void* w_up,
@@ -631,6 +632,7 @@ int diffqkv_augment_q(const diffqkv_augq_shape* shape, const void* q_in, const v
   p.M = shape->M;
   p.K = shape->hidden;
   p.N = shape->inter;
+  p.n_cu = compute_units();
   if (launch_augq(p, shape->dtype, true, mfma, (hipStream_t)hip_stream) != hipSuccess) return DIFFQKV_ERR_HIP;
   p.x = workspace;
   p.w0 = w_down;

@@ -110,6 +110,7 @@ struct AugqParams {
   const void* w1;  // gated only
   void* out;
   int32_t M, K, N;
+  int32_t n_cu;  // compute units of the device (chooses the tile height of the plain pass)
 };
 bool augq_mfma_supported(int dtype, int hidden, int inter);
 hipError_t launch_augq(const AugqParams& p, int dtype, bool gated, bool mfma, hipStream_t s);

@@ -150,7 +150,7 @@ def test_topk_and_augmented_q_validation_codes(lib):
     a = A(16, 2048, 3072, 1)
     assert lib.diffqkv_augment_q_workspace_bytes(ctypes.byref(a)) == 16 * 3072 * 2
     a = A(3, 64, 96, 0)
-    assert lib.diffqkv_augment_q_workspace_bytes(ctypes.byref(a)) == 1280  # 3 x 96 x 4 = 1152, rounded up to 256
+    assert lib.diffqkv_augment_q_workspace_bytes(ctypes.byref(a)) == 16 * 96 * 4  # whole blocks of 16 tokens
 
 
 def test_split_plan_is_a_function_of_shapes(lib):
