@@ -12,7 +12,7 @@
  *     out[b,h,:] = sum_j softmax_j( scale * <q[b,h,:], K[b,kh,j,:]> ) * V[b,vh,j,:],   j < T_b.
  *
  * K is therefore streamed once per K head and V once per V head; nothing is ever expanded to n_q
- * (or to n_v) heads in memory, which is what the cost model of section 3.2 ("KV Cache") counts.
+ * (or to n_v) heads in memory, which is what the cost model of section 3.1 ("KV Cache") counts.
  *
  * Conventions common to all calls
  *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns every
@@ -202,7 +202,7 @@ int diffqkv_decode_topk_paged(const diffqkv_shape* shape /* host */, const void*
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * KV-cache append (section 3.2, "KV Cache": the store side of the cache; K and V are separate
+ * KV-cache append (section 3.1, "KV Cache": the store side of the cache; K and V are separate
  * tensors with their own head counts -- "differential management of KV cache").  For every sequence
  * b, copies k_new[b] into token row positions[b] of the K cache and v_new[b] into the same row of
  * the V cache.  Call it before the attention of the same step: the paper concatenates the current

@@ -231,7 +231,7 @@ def lse_merge(o_parts, lse_parts):
 
 
 def append(k_new, v_new, k_cache, v_cache, positions):
-    """KV-cache store (section 3.2, "KV Cache"): returns copies of the caches with k_new[b], v_new[b]
+    """KV-cache store (section 3.1, "KV Cache"): returns copies of the caches with k_new[b], v_new[b]
     written at token row positions[b]; rows outside [0, T_cap) are skipped.  Plain element copies:
     k_cache [B,n_k,T_cap,d_qk], v_cache [B,n_v,T_cap,d_v], k_new [B,n_k,d_qk], v_new [B,n_v,d_v]."""
     k_out, v_out = np.array(k_cache, copy=True), np.array(v_cache, copy=True)

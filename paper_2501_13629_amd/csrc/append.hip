@@ -1,8 +1,8 @@
 // KV-cache append: store the current token's k_t [n_k, d_qk] and v_t [n_v, d_v] of every sequence
-// at its write position, into a contiguous or a paged cache.  This is the "KV Cache" store of
-// section 3.2: K and V are kept as separate tensors with their own head counts ("differential
-// management of KV cache"), so one token costs (n_k d_qk + n_v d_v) elements -- nothing is
-// duplicated to a common head count.  Pure data movement: 16-byte vector copies, bit exact.
+// at its write position, into a contiguous or a paged cache.  This is the store side of the cache of
+// section 3.2 ("Differential Management of KV Cache"): K and V are kept as separate tensors with their
+// own head counts, so one token costs (n_k d_qk + n_v d_v) elements (the cost model of section 3.1,
+// "KV Cache") -- nothing is duplicated to a common head count.  Pure data movement: 16-byte vector copies, bit exact.
 #include "kernels.h"
 
 namespace diffqkv {

@@ -3,7 +3,7 @@
 // One workgroup (4 wavefronts) owns one (sequence, K head, context chunk).  It streams the chunk's
 // K rows once for all g_k = n_q / n_k query rows under that K head, and the rows of each of the
 // R = n_v / n_k V heads under it once for their g_v = n_q / n_v query rows -- the byte count of the
-// cost model in section 3.2 ("KV Cache"): (n_k d_qk + n_v d_v) elements per token.  The head map is
+// cost model in section 3.1 ("KV Cache"): (n_k d_qk + n_v d_v) elements per token.  The head map is
 // the "idx" rule of section 3.2: query row r of the group reads V head  kh * R + r / g_v.
 //
 // Data path (per wavefront, 32 tokens at a time, no LDS in the loop):

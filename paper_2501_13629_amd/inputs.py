@@ -190,6 +190,6 @@ def as_numpy(t: torch.Tensor) -> np.ndarray:
 
 def kv_bytes_per_token(cfg) -> int:
     """Cache bytes read per (sequence, token): (n_k d_qk + n_v d_v) * element size -- the
-    per-element KV-cache cost model of section 3.2 (equation "cache_0")."""
+    per-element KV-cache cost model of section 3.1 (equation "cache_0")."""
     s = 4 if cfg["dtype"] == "f32" else 2
     return (cfg["n_k"] * cfg["d_qk"] + cfg["n_v"] * cfg["d_v"]) * s

@@ -9,7 +9,7 @@ n_v = 16, head width 64, for n_k = 4 (Sigma) and n_k = 16 (Std), over prefix len
 weights are not needed to time attention: this re-runs the same shapes on seeded random tensors and
 reports, per prefix length, the average split and combine kernel times (HIP events attached to each
 dispatch: the library's experimental kernel timer) and
-the relative saving, next to the cost model's limit (32 - 20) / 32 = 37.5 % (section 3.2).
+the relative saving, next to the cost model's limit (32 - 20) / 32 = 37.5 % (section 3.1).
 """
 import argparse
 import json
