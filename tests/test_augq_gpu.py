@@ -37,6 +37,14 @@ def test_sigma_10b_widths_matrix_cores():
     run(8, 4096, 6144, "bf16", 42)
 
 
+def test_bitwise_repeatable():
+    d = inputs.make_augq(16, 4096, 6144, "bf16", 45)
+    a = [util.dev(d[k]) for k in ("q_in", "w_gate", "w_up", "w_down")]
+    first = binding.diffqkv_augment_q(*a).view(torch.int16).clone()
+    for _ in range(3):
+        assert torch.equal(first, binding.diffqkv_augment_q(*a).view(torch.int16))
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(1, 8, 8), (3, 64, 96), (5, 200, 312), (2, 1024, 1032), (20, 256, 384)])
 def test_portable_kernel_any_width(dtype, shape):

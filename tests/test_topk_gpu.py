@@ -127,6 +127,19 @@ def test_rows_longer_than_the_register_resident_part():
     run(cfg, 512, True, seqlens=[32770])
 
 
+def test_bitwise_repeatable():
+    """Counting in the select kernel uses integer LDS atomics, whose order varies; the selection, the order
+    of the weighted sum and so every output bit do not."""
+    cfg = inputs.config("decode_32k", B=2, T=5000, index=127)
+    d = inputs.make_decode(cfg)
+    q, k, v = util.dev(d["q"]), util.dev(d["k"]), util.dev(d["v"])
+    out, lse, sel = binding.diffqkv_decode_topk(q, k, v, 100, want_lse=True, want_selection=True)
+    a, b, c = out.view(torch.int16).clone(), lse.view(torch.int32).clone(), sel.clone()
+    for _ in range(3):
+        out, lse, sel = binding.diffqkv_decode_topk(q, k, v, 100, want_lse=True, want_selection=True)
+        assert torch.equal(a, out.view(torch.int16)) and torch.equal(b, lse.view(torch.int32)) and torch.equal(c, sel)
+
+
 @pytest.mark.parametrize("page_size", [16, 4])
 def test_paged(page_size):
     cfg = inputs.config("paged_ragged", B=5, seqlens=[1, 17, 700, 1029, 2304], page_size=page_size, index=124)
